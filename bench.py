@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse Winograd forward pass on one MI355X.
+
+A "step" is one pass of the whole hot path (input transform, per-position sparse product,
+output transform) over one batch of seeded synthetic input that is already resident in HBM.
+Metric: effective TFLOP/s = FLOPs a dense direct convolution would execute / time (the paper's
+Fig. 2 definition).  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--density D]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+FP32_VECTOR_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CU x 128 FMA lanes x 2 x 2.4 GHz)
+STAGES = ("input_transform_kernel", "spmm_kernel", "output_transform_kernel")
+
+
+def stage_models(cfg, nnz):
+    """Algorithmic bytes and flops of each of the three kernels for one launch."""
+    N, C, H, W, K = cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"]
+    P, T, Ho, Wo = cfg["P"], cfg["T"], cfg["Ho"], cfg["Wo"]
+    return [
+        dict(bytes=4 * (N * C * H * W + P * C * T), flops=0),
+        dict(bytes=4 * (P * C * T + P * K * T) + 8 * nnz, flops=2 * nnz * T),
+        dict(bytes=4 * (P * K * T + N * K * Ho * Wo), flops=0),
+    ]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--workload", default=None)
+    ap.add_argument("--density", type=float, default=None)
+    ap.add_argument("--dense", action="store_true", help="time the 0%%-sparsity MFMA comparison path instead")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the forward path has no multi-GPU part); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_1702_08597_amd import binding as sw
+    from paper_1702_08597_amd import synth
+
+    name = args.workload or synth.BENCH_CONFIG
+    cfg, x, rp, ci, va = synth.make_layer(name, density=args.density)
+    nnz = int(rp[-1])
+    flops_direct = synth.direct_conv_flops(cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"], cfg["m"], cfg["r"],
+                                           cfg["pad"])
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    plan = sw.swconv_plan_create(cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"], cfg["m"], cfg["r"], cfg["pad"])
+    xd = torch.from_numpy(x).to(dev)
+    out = torch.empty((cfg["N"], cfg["K"], cfg["Ho"], cfg["Wo"]), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    sp, xp, op = stream.cuda_stream, xd.data_ptr(), out.data_ptr()
+    if args.dense:
+        wf = synth.dense_weights(cfg["P"], cfg["K"], cfg["C"], cfg["seed"] + 2000)
+        sw.swconv_set_weights_dense(plan, wf)
+        step = lambda: sw.swconv_forward_dense(plan, sp, xp, op)
+    else:
+        t0 = time.perf_counter()
+        sw.swconv_set_weights(plan, rp, ci, va)
+        set_weights_ms = (time.perf_counter() - t0) * 1e3
+        step = lambda: sw.swconv_forward(plan, sp, xp, op)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    value = flops_direct / (elapsed / args.steps) / 1e12
+
+    result = {
+        "metric": "effective TFLOP/s (direct-conv FLOPs / time), 1 MI355X",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": name, "N": cfg["N"], "C": cfg["C"], "H": cfg["H"], "W": cfg["W"], "K": cfg["K"],
+                   "winograd": "F(%dx%d,3x3)" % (cfg["m"], cfg["m"]), "pad": cfg["pad"],
+                   "density": (nnz / float(cfg["P"] * cfg["K"] * cfg["C"])), "nnz": nnz,
+                   "path": "dense-mfma-comparison" if args.dense else "sparse"},
+        "paper_context": {"value": 31.7, "unit": "effective TFLOP/s fp32", "hardware": "2x Xeon Platinum 8180 (56 cores)",
+                          "note": "paper's peak on pruned AlexNet 3x3 layers, batch 56; another machine and model"},
+    }
+
+    if not args.dense:
+        # per-kernel durations: HIP events on the launch stream around each kernel, over the same
+        # number of steps as the timed region
+        stage_ms = sw.swconv_profile_forward(plan, sp, xp, op, args.steps)
+        models = stage_models(cfg, nnz)
+        stages = []
+        for nm, ms, mdl in zip(STAGES, stage_ms.tolist(), models):
+            gbs = mdl["bytes"] / (ms * 1e-3) / 1e9
+            tfl = mdl["flops"] / (ms * 1e-3) / 1e12
+            stages.append({"kernel": nm, "ms": round(ms, 6), "alg_bytes": mdl["bytes"], "alg_flops": mdl["flops"],
+                           "GBps": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4),
+                           "TFLOPs": round(tfl, 3), "fp32_frac": round(tfl / FP32_VECTOR_TFLOPS, 4)})
+        dom = max(range(3), key=lambda i: stage_ms[i])
+        d, mdl = stages[dom], models[dom]
+        t_hbm = mdl["bytes"] / (HBM_PEAK_GBS * 1e9)
+        t_alu = mdl["flops"] / (FP32_VECTOR_TFLOPS * 1e12)
+        if t_hbm >= t_alu:
+            roof = {"bound": "hbm", "achieved": d["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(d["GBps"] / HBM_PEAK_GBS, 4)}
+        else:
+            roof = {"bound": "alu", "achieved": d["TFLOPs"], "peak": FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(d["TFLOPs"] / FP32_VECTOR_TFLOPS, 4)}
+        roof.update({"kernel": d["kernel"], "avg_ms": d["ms"], "traffic": None})
+        result["roofline"] = roof
+        result["stages"] = stages
+        st = sw.swconv_plan_weight_stats(plan)
+        result["weights"] = {"set_weights_ms": round(set_weights_ms, 3), "padded_nnz": st["padded_nnz"],
+                             "work_items": st["work_items"]}
+
+    if not args.no_cpu_baseline:
+        import oracle
+
+        # the oracle's float instantiation, as it stands, on the host cores of this machine
+        n_img = cfg["N"]
+        xs = x
+        t_one = None
+        times = []
+        budget = 20.0
+        t_start = time.perf_counter()
+        while True:
+            t0 = time.perf_counter()
+            oracle.forward_f32(xs, rp, ci, va, cfg["K"], cfg["m"], cfg["r"], cfg["pad"])
+            times.append(time.perf_counter() - t0)
+            if len(times) >= 5 or time.perf_counter() - t_start > budget:
+                break
+        t_med = sorted(times)[len(times) // 2]
+        result["cpu_baseline"] = {"value": round(flops_direct / t_med / 1e12, 5), "unit": "TFLOP/s",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": "full workload (%d images), median of %d runs, fp32 instantiation"
+                                            % (n_img, len(times)),
+                                  "seconds": round(t_med, 4)}
+
+    sw.swconv_plan_destroy(plan)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,163 @@
+/*
+ * swconv - sparse Winograd convolution forward pass for AMD MI355X (gfx950).
+ *
+ * C ABI.  Plain pointers and sizes only; every pointer argument is marked HOST or DEVICE.
+ *
+ * The library computes the "Winograd layer" of arxiv 1702.08597, Section 3, Eq. 4:
+ *
+ *     O~(k,tau,:,:) = A^T [ sum_c W_F(k,c,:,:) (.) ( B^T I~(c,tau,:,:) B ) ] A
+ *
+ * with W_F a free, natively pruned (sparse) K x C x t x t parameter tensor, t = m + r - 1,
+ * in the three steps Section 5 names:
+ *   (1) input transform   V[p][c][tau] = (B^T d B)[i][j],  d = the t x t input tile of (c,tau)
+ *   (2) per-position sparse x dense product   M[p] = W_F[p] * V[p]   (K x C times C x T),
+ *       one for each of the P = t*t Winograd positions p = i*t + j  (remark after Eq. 4's
+ *       intermediate variables; Section 5 calls it SpMDM and the bulk of the computation)
+ *   (3) output transform  Y = A^T m^ A,  m^[i][j] = M[i*t+j][k][tau], scattered to the output.
+ *
+ * Conventions (where the paper is silent, these readings are part of the contract):
+ *   - fp32 data, int32 indices.  Unit stride and dilation, square r x r kernel, square m x m
+ *     output tile (Section 3 assumes unit stride/dilation; A1=A2, B1=B2 when r=s, m=n).
+ *   - Supported F(m x m, r x r): (m,r) = (2,3) and (4,3).  A, B are the standard
+ *     minimal-filtering matrices for points {0,1,-1,inf} and {0,1,-1,2,-2,inf} (the paper defers
+ *     to Lavin & Gray for their values):
+ *       F(2,3): B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1],  A^T = [1 1 1 0; 0 1 -1 -1]
+ *       F(4,3): B^T = [4 0 -5 0 1 0; 0 -4 -4 1 1 0; 0 4 -4 -1 1 0; 0 -2 -1 2 1 0;
+ *                      0 2 -1 -2 1 0; 0 4 0 -5 0 1]
+ *               A^T = [1 1 1 1 1 0; 0 1 -1 2 -2 0; 0 1 1 4 4 0; 0 1 -1 8 -8 1]
+ *   - Ho = H + 2*pad - r + 1, Wo likewise; th = ceil(Ho/m), tw = ceil(Wo/m); T = N*th*tw.
+ *     Tile tau = (n*th + ty)*tw + tx reads input rows ty*m - pad ... ty*m - pad + t - 1 (zero
+ *     outside the image: this covers both the convolution padding and a ragged last tile, per
+ *     the footnote to the divisibility assumption in Section 3) and owns output rows
+ *     ty*m ... ty*m + m - 1; outputs outside Ho x Wo are computed and dropped.
+ *   - Inputs must be finite: a structural zero of W_F is skipped, not multiplied.
+ *
+ * Every function returns a swconv_status (0 = success); nothing throws or aborts across the
+ * ABI; output arguments are untouched on failure unless stated otherwise.
+ */
+#ifndef SWCONV_H
+#define SWCONV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct swconv_plan swconv_plan; /* opaque, owned by the library */
+
+typedef enum {
+  SWCONV_OK = 0,
+  SWCONV_EINVAL = 1,       /* bad shape, null pointer, malformed CSR                 */
+  SWCONV_EUNSUPPORTED = 2, /* (m,r) other than (2,3),(4,3); sizes beyond the kernels */
+  SWCONV_ENOMEM = 3,       /* host or device allocation failed                       */
+  SWCONV_EHIP = 4,         /* HIP runtime error (no device, launch failure, ...)     */
+  SWCONV_ESTATE = 5        /* forward before weights were set                        */
+} swconv_status;
+
+/* Human-readable name of a status code; never NULL; static storage. */
+const char* swconv_status_string(int status);
+
+/*
+ * Create a plan for one layer shape (Eq. 1/Eq. 4 dimensions: N images, C input channels of
+ * H x W, K output channels; F(m x m, r x r); zero padding `pad` on all four sides).
+ * Touches no device: device buffers (V, M workspaces, packed weights) are allocated by the
+ * first swconv_set_weights / swconv_set_weights_dense on the then-current HIP device.
+ * Errors: EINVAL for non-positive sizes, pad < 0, Ho or Wo < 1 or index ranges beyond int32;
+ * EUNSUPPORTED for an unsupported (m,r) or a shape whose panels do not fit the kernels' LDS
+ * budget (C > 640).  On success *out owns the plan; release with swconv_plan_destroy.
+ */
+int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int m, int r, int pad);
+
+/* Frees the plan and every host and device buffer it owns.  NULL is allowed. */
+void swconv_plan_destroy(swconv_plan* plan);
+
+/*
+ * Set the pruned Winograd-domain weights as per-position CSR (Section 2 names CSR as the
+ * general sparse format; Section 5: one sparse K x C matrix per position).
+ *   rowptr  HOST, P*K + 1 entries, rowptr[0] = 0, non-decreasing, global offsets: row (p,k)
+ *           is [rowptr[p*K + k], rowptr[p*K + k + 1]).
+ *   colidx  HOST, nnz = rowptr[P*K] entries, 0 <= c < C, strictly ascending within a row.
+ *   vals    HOST, nnz entries; vals[q] = W_F[k][c][i][j] with p = i*t + j.  Stored zeros are
+ *           legal and are treated as non-zeros.  nnz = 0 is legal (colidx/vals may be NULL).
+ * The arrays are validated, re-packed into the kernels' sliced layout (rows of a position
+ * sorted by length, grouped four at a time, padded with zero weights) together with a
+ * load-balanced work list, and copied to the device before the call returns; the caller keeps
+ * ownership of its arrays.  May be called again with a new pattern.  Blocks the host.
+ * Errors: EINVAL on any CSR violation (the plan keeps its previous weights); ENOMEM; EHIP when
+ * no device is usable - the host-side packed copy is still kept in that case, so
+ * swconv_debug_export_weights works without a GPU.
+ */
+int swconv_set_weights(swconv_plan* plan, const int32_t* rowptr, const int32_t* colidx, const float* vals);
+
+/*
+ * Forward pass of Eq. 4 with the sparse weights: three kernels (Section 5's steps 1-3)
+ * enqueued on `hip_stream` (a hipStream_t; NULL = the default stream).  Asynchronous: returns
+ * after enqueueing, does not synchronise.
+ *   in_dev   DEVICE, N x C x H x W fp32, contiguous (W fastest), read-only.
+ *   out_dev  DEVICE, N x K x Ho x Wo fp32, contiguous; every element is overwritten.
+ * The two must not alias and must live on the device the weights were set on.  The plan owns
+ * the V and M workspaces, so one plan must not run on two streams at once.
+ * Errors: EINVAL (null), ESTATE (no weights), EHIP (launch failure).
+ */
+int swconv_forward(swconv_plan* plan, void* hip_stream, const float* in_dev, float* out_dev);
+
+/*
+ * The 0 %-sparsity comparison: the same layer with a dense W_F, computed with the same
+ * transforms and a dense batched fp32 MFMA product for step 2.  Not the paper's method - the
+ * paper has no dense Winograd implementation and projects one (Section 6.2); this is the
+ * in-house baseline the sparse path is compared with.
+ *   wf  HOST, [P][K][C] fp32, wf[p][k][c] = W_F[k][c][i][j].
+ * Errors as for swconv_set_weights / swconv_forward.
+ */
+int swconv_set_weights_dense(swconv_plan* plan, const float* wf);
+int swconv_forward_dense(swconv_plan* plan, void* hip_stream, const float* in_dev, float* out_dev);
+
+/*
+ * Measurement helper: run `iters` sparse forward passes on `hip_stream` with HIP events
+ * recorded on that stream around each of the three kernels, synchronise, and return the
+ * mean duration of each step in milliseconds.
+ *   stage_ms  HOST, 3 floats: input transform, sparse product, output transform.
+ * Blocks the host.  Errors as for swconv_forward; EINVAL for iters < 1.
+ */
+int swconv_profile_forward(swconv_plan* plan, void* hip_stream, const float* in_dev, float* out_dev, int iters,
+                           float* stage_ms);
+
+/*
+ * Test hooks (not on the timed path).  They synchronise the device and copy the intermediates
+ * of the last forward into caller buffers in the canonical layouts of the definition above.
+ *   V_host  HOST, [P][C][T] fp32        M_host  HOST, [P][K][T] fp32
+ * Errors: ESTATE when no forward has run; EHIP.
+ */
+int swconv_debug_copy_V(swconv_plan* plan, float* V_host);
+int swconv_debug_copy_M(swconv_plan* plan, float* M_host);
+
+/*
+ * Round trip of the re-packed sparse weights: unpacks the host-side copy of the sliced layout
+ * back to per-position CSR (padding dropped, rows back in their original order).
+ *   rowptr HOST P*K + 1 entries; colidx, vals HOST nnz entries each (nnz as passed to
+ *   swconv_set_weights).  The result equals that call's arrays bit for bit.
+ * Errors: ESTATE when no sparse weights were set.
+ */
+int swconv_debug_export_weights(swconv_plan* plan, int32_t* rowptr, int32_t* colidx, float* vals);
+
+/*
+ * Sizes derived by the plan (any pointer may be NULL): positions P, tiles T, Ho, Wo.
+ */
+int swconv_plan_sizes(const swconv_plan* plan, int* P, int64_t* T, int* Ho, int* Wo);
+
+/*
+ * Statistics of the packed weights and the work list built by swconv_set_weights:
+ *   nnz          stored entries as passed in
+ *   padded_nnz   entries after padding to the sliced layout (what the kernel multiplies)
+ *   work_items   entries of the load-balanced work list (per tile block)
+ *   max_item     padded entries in the heaviest work item
+ * Errors: ESTATE when no sparse weights were set.
+ */
+int swconv_plan_weight_stats(const swconv_plan* plan, int64_t* nnz, int64_t* padded_nnz, int* work_items,
+                             int64_t* max_item);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWCONV_H */

@@ -1,0 +1,160 @@
+"""Thin ctypes binding of libswconv.so: the same entry points as include/swconv.h, argument
+marshalling only.  Every step of the forward pass runs in the library's HIP kernels; there is no
+fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+SWCONV_OK, SWCONV_EINVAL, SWCONV_EUNSUPPORTED, SWCONV_ENOMEM, SWCONV_EHIP, SWCONV_ESTATE = range(6)
+
+EXPORTS = [
+    "swconv_status_string", "swconv_plan_create", "swconv_plan_destroy", "swconv_set_weights",
+    "swconv_forward", "swconv_set_weights_dense", "swconv_forward_dense", "swconv_profile_forward",
+    "swconv_debug_copy_V", "swconv_debug_copy_M", "swconv_debug_export_weights", "swconv_plan_sizes",
+    "swconv_plan_weight_stats",
+]
+
+_lib = None
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_f32p = ctypes.POINTER(ctypes.c_float)
+_vp = ctypes.c_void_p
+
+
+class SwconvError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, swconv_status_string(status)))
+
+
+def lib():
+    """Load libswconv.so (building it only if no built library is present)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build_library()
+        L = ctypes.CDLL(_build.LIB)
+        L.swconv_status_string.restype = ctypes.c_char_p
+        L.swconv_status_string.argtypes = [ctypes.c_int]
+        L.swconv_plan_create.argtypes = [ctypes.POINTER(_vp)] + [ctypes.c_int] * 8
+        L.swconv_plan_destroy.argtypes = [_vp]
+        L.swconv_plan_destroy.restype = None
+        L.swconv_set_weights.argtypes = [_vp, _i32p, _i32p, _f32p]
+        L.swconv_forward.argtypes = [_vp, _vp, _vp, _vp]
+        L.swconv_set_weights_dense.argtypes = [_vp, _f32p]
+        L.swconv_forward_dense.argtypes = [_vp, _vp, _vp, _vp]
+        L.swconv_profile_forward.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int, _f32p]
+        L.swconv_debug_copy_V.argtypes = [_vp, _f32p]
+        L.swconv_debug_copy_M.argtypes = [_vp, _f32p]
+        L.swconv_debug_export_weights.argtypes = [_vp, _i32p, _i32p, _f32p]
+        L.swconv_plan_sizes.argtypes = [_vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int64),
+                                        ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+        L.swconv_plan_weight_stats.argtypes = [_vp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
+                                               ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int64)]
+        _lib = L
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None and a.size else None
+
+
+def _check(status, where):
+    if status != SWCONV_OK:
+        raise SwconvError(status, where)
+
+
+def swconv_status_string(status):
+    return lib().swconv_status_string(int(status)).decode()
+
+
+def swconv_plan_create(N, C, H, W, K, m, r, pad):
+    """-> opaque plan handle (int).  Raises SwconvError with the library's status."""
+    h = _vp()
+    _check(lib().swconv_plan_create(ctypes.byref(h), N, C, H, W, K, m, r, pad), "swconv_plan_create")
+    return h
+
+
+def swconv_plan_destroy(plan):
+    lib().swconv_plan_destroy(plan)
+
+
+def swconv_set_weights(plan, rowptr, colidx, vals):
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    _check(lib().swconv_set_weights(plan, rowptr.ctypes.data_as(_i32p), _p(colidx, ctypes.c_int32),
+                                    _p(vals, ctypes.c_float)), "swconv_set_weights")
+
+
+def swconv_set_weights_status(plan, rowptr, colidx, vals):
+    """Same call, returning the raw status instead of raising (for error-path tests)."""
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    return lib().swconv_set_weights(plan, rowptr.ctypes.data_as(_i32p), _p(colidx, ctypes.c_int32),
+                                    _p(vals, ctypes.c_float))
+
+
+def swconv_forward(plan, stream, in_dev_ptr, out_dev_ptr):
+    """stream: hipStream_t as int (0 = default); in/out: device addresses as int."""
+    _check(lib().swconv_forward(plan, _vp(stream), _vp(in_dev_ptr), _vp(out_dev_ptr)), "swconv_forward")
+
+
+def swconv_set_weights_dense(plan, wf):
+    wf = np.ascontiguousarray(wf, dtype=np.float32)
+    _check(lib().swconv_set_weights_dense(plan, wf.ctypes.data_as(_f32p)), "swconv_set_weights_dense")
+
+
+def swconv_forward_dense(plan, stream, in_dev_ptr, out_dev_ptr):
+    _check(lib().swconv_forward_dense(plan, _vp(stream), _vp(in_dev_ptr), _vp(out_dev_ptr)), "swconv_forward_dense")
+
+
+def swconv_profile_forward(plan, stream, in_dev_ptr, out_dev_ptr, iters):
+    """-> numpy float32[3]: mean milliseconds of the input transform, sparse product, output transform."""
+    ms = np.zeros(3, dtype=np.float32)
+    _check(lib().swconv_profile_forward(plan, _vp(stream), _vp(in_dev_ptr), _vp(out_dev_ptr), int(iters),
+                                        ms.ctypes.data_as(_f32p)), "swconv_profile_forward")
+    return ms
+
+
+def swconv_plan_sizes(plan):
+    P, T, Ho, Wo = ctypes.c_int(), ctypes.c_int64(), ctypes.c_int(), ctypes.c_int()
+    _check(lib().swconv_plan_sizes(plan, ctypes.byref(P), ctypes.byref(T), ctypes.byref(Ho), ctypes.byref(Wo)),
+           "swconv_plan_sizes")
+    return P.value, T.value, Ho.value, Wo.value
+
+
+def swconv_plan_weight_stats(plan):
+    a, b, c, d = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int(), ctypes.c_int64()
+    _check(lib().swconv_plan_weight_stats(plan, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d)),
+           "swconv_plan_weight_stats")
+    return dict(nnz=a.value, padded_nnz=b.value, work_items=c.value, max_item=d.value)
+
+
+def swconv_debug_copy_V(plan, C):
+    P, T, _, _ = swconv_plan_sizes(plan)
+    V = np.empty((P, C, T), dtype=np.float32)
+    _check(lib().swconv_debug_copy_V(plan, V.ctypes.data_as(_f32p)), "swconv_debug_copy_V")
+    return V
+
+
+def swconv_debug_copy_M(plan, K):
+    P, T, _, _ = swconv_plan_sizes(plan)
+    M = np.empty((P, K, T), dtype=np.float32)
+    _check(lib().swconv_debug_copy_M(plan, M.ctypes.data_as(_f32p)), "swconv_debug_copy_M")
+    return M
+
+
+def swconv_debug_export_weights(plan, K, nnz):
+    P, _, _, _ = swconv_plan_sizes(plan)
+    rowptr = np.empty(P * K + 1, dtype=np.int32)
+    colidx = np.empty(nnz, dtype=np.int32)
+    vals = np.empty(nnz, dtype=np.float32)
+    _check(lib().swconv_debug_export_weights(plan, rowptr.ctypes.data_as(_i32p), _p(colidx, ctypes.c_int32),
+                                             _p(vals, ctypes.c_float)), "swconv_debug_export_weights")
+    return rowptr, colidx, vals

@@ -1,0 +1,494 @@
+// Host side of libswconv: plan, CSR validation and re-packing, work-list construction, launches.
+// Implements the C ABI declared in include/swconv.h.
+#include "../../include/swconv.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "swconv_dense_mfma.hpp"
+#include "swconv_kernels.hpp"
+
+using namespace swconv;
+
+namespace {
+
+constexpr int kSpmmWaves = 8;       // waves per SpMM workgroup
+constexpr int kMaxLdsBytes = 160 * 1024;
+constexpr int kSliceOverhead = 6;   // cost of starting/finishing a slice, in slots
+
+int env_int(const char* name, int dflt) {
+  const char* s = std::getenv(name);
+  if (!s || !*s) return dflt;
+  char* end = nullptr;
+  long v = std::strtol(s, &end, 10);
+  return (end && *end == 0) ? (int)v : dflt;
+}
+
+#define HIP_TRY(expr)                         \
+  do {                                        \
+    hipError_t e_ = (expr);                   \
+    if (e_ != hipSuccess) {                   \
+      (void)hipGetLastError();                \
+      return e_ == hipErrorOutOfMemory ? SWCONV_ENOMEM : SWCONV_EHIP; \
+    }                                         \
+  } while (0)
+
+template <typename T>
+int upload(T** dptr, const std::vector<T>& h) {
+  if (*dptr) {
+    (void)hipFree(*dptr);
+    *dptr = nullptr;
+  }
+  const size_t bytes = std::max<size_t>(h.size(), 1) * sizeof(T);
+  HIP_TRY(hipMalloc((void**)dptr, bytes));
+  if (!h.empty()) HIP_TRY(hipMemcpy(*dptr, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice));
+  return SWCONV_OK;
+}
+
+}  // namespace
+
+struct swconv_plan {
+  Geometry g{};
+  int m = 0, r = 0, t = 0, P = 0;
+  int tpl = 1;   // tiles per lane in the sparse product
+  int tb = 64;   // tile block = 64 * tpl
+  int Kp = 0;    // K rounded up to a multiple of the slice height
+  int Kq = 0;    // K rounded up to the dense GEMM's row tile
+  int n_tau_blocks = 0;
+
+  // host-side packed sparse weights
+  bool have_sparse = false;
+  int64_t nnz = 0, padded_nnz = 0, max_item = 0;
+  std::vector<uint32_t> stream;      // 8 dwords per slot: c0..c3, w0..w3
+  std::vector<Slice> slices;         // P * Kp/4
+  std::vector<int32_t> sorted_rows;  // P * Kp: original row k of each sorted row, -1 = padding
+  std::vector<int32_t> sorted_len;   // P * Kp: stored entries of each sorted row
+  std::vector<WorkItem> items;
+
+  // device
+  bool on_device = false, sparse_on_device = false, dense_on_device = false, ran_forward = false;
+  float *dV = nullptr, *dM = nullptr;
+  uint32_t* d_stream = nullptr;
+  Slice* d_slices = nullptr;
+  int32_t* d_sorted_rows = nullptr;
+  WorkItem* d_items = nullptr;
+  float* d_wdense = nullptr;  // [P][C][Kq]
+};
+
+namespace {
+
+int ensure_workspace(swconv_plan* pl) {
+  if (pl->on_device) return SWCONV_OK;
+  int ndev = 0;
+  HIP_TRY(hipGetDeviceCount(&ndev));
+  if (ndev < 1) return SWCONV_EHIP;
+  const size_t vbytes = (size_t)pl->P * pl->g.C * pl->g.Tp * sizeof(float);
+  const size_t mbytes = (size_t)pl->P * pl->g.K * pl->g.Tp * sizeof(float);
+  HIP_TRY(hipMalloc((void**)&pl->dV, vbytes));
+  HIP_TRY(hipMalloc((void**)&pl->dM, mbytes));
+  HIP_TRY(hipMemset(pl->dV, 0, vbytes));
+  HIP_TRY(hipMemset(pl->dM, 0, mbytes));
+  pl->on_device = true;
+  return SWCONV_OK;
+}
+
+template <int M>
+int launch_input_transform(const swconv_plan* pl, hipStream_t st, const float* in) {
+  dim3 grid(pl->g.Tp / 64, (pl->g.C + 3) / 4);
+  hipLaunchKernelGGL(input_transform_kernel<M>, grid, dim3(256), 0, st, in, pl->dV, pl->g);
+  HIP_TRY(hipGetLastError());
+  return SWCONV_OK;
+}
+
+template <int M>
+int launch_output_transform(const swconv_plan* pl, hipStream_t st, float* out) {
+  dim3 grid(pl->g.Tp / 64, (pl->g.K + 3) / 4);
+  hipLaunchKernelGGL(output_transform_kernel<M>, grid, dim3(256), 0, st, pl->dM, out, pl->g);
+  HIP_TRY(hipGetLastError());
+  return SWCONV_OK;
+}
+
+template <int TPL>
+int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
+  const int n_items = (int)pl->items.size();
+  if (n_items == 0) return SWCONV_OK;
+  const size_t lds = (size_t)pl->g.C * 64 * TPL * sizeof(float);
+  auto kern = spmm_kernel<TPL, kSpmmWaves>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(n_items), dim3(kSpmmWaves * 64), lds, st, pl->dV, pl->dM, pl->d_stream,
+                     pl->d_slices, pl->d_sorted_rows, pl->d_items, n_items, pl->g.C, pl->g.K, pl->g.Tp);
+  HIP_TRY(hipGetLastError());
+  return SWCONV_OK;
+}
+
+int launch_spmm(const swconv_plan* pl, hipStream_t st) {
+  return pl->tpl == 2 ? launch_spmm_t<2>(pl, st) : launch_spmm_t<1>(pl, st);
+}
+
+int launch_stage(const swconv_plan* pl, hipStream_t st, int stage, const float* in, float* out) {
+  switch (stage) {
+    case 0: return pl->m == 2 ? launch_input_transform<2>(pl, st, in) : launch_input_transform<4>(pl, st, in);
+    case 1: return launch_spmm(pl, st);
+    default: return pl->m == 2 ? launch_output_transform<2>(pl, st, out) : launch_output_transform<4>(pl, st, out);
+  }
+}
+
+// Validate the caller's CSR; returns SWCONV_OK or SWCONV_EINVAL.
+int validate_csr(const swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, const float* vals) {
+  const int64_t rows = (int64_t)pl->P * pl->g.K;
+  if (!rowptr || rowptr[0] != 0) return SWCONV_EINVAL;
+  for (int64_t i = 0; i < rows; ++i)
+    if (rowptr[i + 1] < rowptr[i]) return SWCONV_EINVAL;
+  const int64_t nnz = rowptr[rows];
+  if (nnz > 0 && (!colidx || !vals)) return SWCONV_EINVAL;
+  for (int64_t i = 0; i < rows; ++i) {
+    if (rowptr[i + 1] - rowptr[i] > pl->g.C) return SWCONV_EINVAL;
+    int32_t prev = -1;
+    for (int32_t q = rowptr[i]; q < rowptr[i + 1]; ++q) {
+      const int32_t c = colidx[q];
+      if (c <= prev || c >= pl->g.C) return SWCONV_EINVAL;
+      prev = c;
+    }
+  }
+  return SWCONV_OK;
+}
+
+// Re-pack per-position CSR into the sliced layout and build the work list.
+void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, const float* vals) {
+  const int P = pl->P, K = pl->g.K, Kp = pl->Kp;
+  const int slices_per_pos = Kp / kSliceRows;
+  pl->nnz = rowptr[(int64_t)P * K];
+  pl->sorted_rows.assign((size_t)P * Kp, -1);
+  pl->sorted_len.assign((size_t)P * Kp, 0);
+  pl->slices.assign((size_t)P * slices_per_pos, Slice{});
+
+  std::vector<int32_t> order(K);
+  std::vector<int64_t> pos_cost(P, 0);
+  uint64_t slot_cursor = 0;
+  for (int p = 0; p < P; ++p) {
+    const int32_t* rp = rowptr + (int64_t)p * K;
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return rp[a + 1] - rp[a] > rp[b + 1] - rp[b]; });
+    for (int i = 0; i < K; ++i) {
+      pl->sorted_rows[(size_t)p * Kp + i] = order[i];
+      pl->sorted_len[(size_t)p * Kp + i] = rp[order[i] + 1] - rp[order[i]];
+    }
+    for (int s = 0; s < slices_per_pos; ++s) {
+      Slice& sl = pl->slices[(size_t)p * slices_per_pos + s];
+      sl.p = p;
+      sl.row0 = p * Kp + s * kSliceRows;
+      sl.len = pl->sorted_len[sl.row0];  // rows are sorted: the first is the longest
+      sl.slot0 = (uint32_t)slot_cursor;
+      slot_cursor += sl.len;
+      pos_cost[p] += sl.len + kSliceOverhead;
+    }
+  }
+  pl->padded_nnz = (int64_t)slot_cursor * kSliceRows;
+  pl->stream.assign((size_t)slot_cursor * 8, 0u);  // column 0, weight +0.0f
+  for (size_t s = 0; s < pl->slices.size(); ++s) {
+    const Slice& sl = pl->slices[s];
+    const int32_t* rp = rowptr + (int64_t)sl.p * K;
+    for (int r = 0; r < kSliceRows; ++r) {
+      const int k = pl->sorted_rows[sl.row0 + r];
+      if (k < 0) continue;
+      const int32_t q0 = rp[k], len = rp[k + 1] - rp[k];
+      for (int32_t e = 0; e < len; ++e) {
+        uint32_t* slot = pl->stream.data() + ((size_t)sl.slot0 + e) * 8;
+        slot[r] = (uint32_t)colidx[q0 + e];
+        std::memcpy(&slot[4 + r], &vals[q0 + e], sizeof(float));
+      }
+    }
+  }
+
+  // Work list.  Each position is cut into a number of strided slice subsets proportional to
+  // its cost, so that all workgroups carry about the same number of slots whatever the
+  // per-position densities are; positions stay contiguous in the list (one XCD's L2 then holds
+  // the panels and the weights of the few positions it works on).
+  const int64_t total_cost = std::accumulate(pos_cost.begin(), pos_cost.end(), (int64_t)0);
+  const int target_wgs = env_int("SWCONV_SPMM_TARGET_WGS", 1024);
+  const int min_slices_per_wg = std::max(1, env_int("SWCONV_SPMM_MIN_SLICES", kSpmmWaves));
+  const int64_t target_items = std::max<int64_t>(P, (target_wgs + pl->n_tau_blocks - 1) / pl->n_tau_blocks);
+  const int64_t cost_per_item = std::max<int64_t>(1, (total_cost + target_items - 1) / target_items);
+  pl->items.clear();
+  pl->max_item = 0;
+  for (int p = 0; p < P; ++p) {
+    int chunks = (int)((pos_cost[p] + cost_per_item - 1) / cost_per_item);
+    chunks = std::max(1, std::min(chunks, std::max(1, slices_per_pos / min_slices_per_wg)));
+    const int s0 = p * slices_per_pos, s1 = s0 + slices_per_pos;
+    for (int tb = 0; tb < pl->n_tau_blocks; ++tb) {
+      for (int ch = 0; ch < chunks; ++ch) {
+        pl->items.push_back(WorkItem{p, tb, s0 + ch, s1, chunks});
+        int64_t slots = 0;
+        for (int s = s0 + ch; s < s1; s += chunks) slots += pl->slices[s].len;
+        pl->max_item = std::max(pl->max_item, slots * kSliceRows);
+      }
+    }
+  }
+  pl->have_sparse = true;
+}
+
+int upload_sparse(swconv_plan* pl) {
+  int rc = ensure_workspace(pl);
+  if (rc) return rc;
+  pl->sparse_on_device = false;
+  if ((rc = upload(&pl->d_stream, pl->stream))) return rc;
+  if ((rc = upload(&pl->d_slices, pl->slices))) return rc;
+  if ((rc = upload(&pl->d_sorted_rows, pl->sorted_rows))) return rc;
+  if ((rc = upload(&pl->d_items, pl->items))) return rc;
+  HIP_TRY(hipDeviceSynchronize());
+  pl->sparse_on_device = true;
+  return SWCONV_OK;
+}
+
+int copy_padded_to_host(const float* dsrc, float* hdst, size_t rows, int T, int Tp) {
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipMemcpy2D(hdst, (size_t)T * sizeof(float), dsrc, (size_t)Tp * sizeof(float), (size_t)T * sizeof(float),
+                      rows, hipMemcpyDeviceToHost));
+  return SWCONV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* swconv_status_string(int status) {
+  switch (status) {
+    case SWCONV_OK: return "SWCONV_OK";
+    case SWCONV_EINVAL: return "SWCONV_EINVAL: invalid argument";
+    case SWCONV_EUNSUPPORTED: return "SWCONV_EUNSUPPORTED: unsupported configuration";
+    case SWCONV_ENOMEM: return "SWCONV_ENOMEM: out of memory";
+    case SWCONV_EHIP: return "SWCONV_EHIP: HIP runtime error";
+    case SWCONV_ESTATE: return "SWCONV_ESTATE: weights not set or no forward pass yet";
+    default: return "unknown swconv status";
+  }
+}
+
+int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int m, int r, int pad) {
+  if (!out) return SWCONV_EINVAL;
+  if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || pad < 0 || m < 1 || r < 1) return SWCONV_EINVAL;
+  if (!((m == 2 && r == 3) || (m == 4 && r == 3))) return SWCONV_EUNSUPPORTED;
+  const int64_t Ho = (int64_t)H + 2 * pad - r + 1, Wo = (int64_t)W + 2 * pad - r + 1;
+  if (Ho < 1 || Wo < 1) return SWCONV_EINVAL;
+  const int t = m + r - 1, P = t * t;
+  const int64_t th = (Ho + m - 1) / m, tw = (Wo + m - 1) / m;
+  const int64_t T = (int64_t)N * th * tw;
+  const int64_t lim = (int64_t)1 << 31;
+  // every flat index the kernels form in 32 bits, and the CSR offsets, must fit int32
+  if (T + 128 >= lim || (int64_t)P * K * C >= lim || (int64_t)H * W >= lim || Ho * Wo >= lim ||
+      (int64_t)N * C * H * W >= ((int64_t)1 << 40) || (int64_t)P * (K + 4) >= lim)
+    return SWCONV_EINVAL;
+
+  swconv_plan* pl = new (std::nothrow) swconv_plan();
+  if (!pl) return SWCONV_ENOMEM;
+  // tile block: two tiles per lane when the C x 128 panel still lets two workgroups share a CU
+  int tpl = env_int("SWCONV_SPMM_TPL", 0);
+  if (tpl != 1 && tpl != 2) tpl = 1;
+  if ((int64_t)C * 64 * tpl * (int64_t)sizeof(float) > kMaxLdsBytes) tpl = 1;
+  if ((int64_t)C * 64 * (int64_t)sizeof(float) > kMaxLdsBytes) {
+    delete pl;
+    return SWCONV_EUNSUPPORTED;
+  }
+  pl->m = m;
+  pl->r = r;
+  pl->t = t;
+  pl->P = P;
+  pl->tpl = tpl;
+  pl->tb = 64 * tpl;
+  pl->Kp = (K + kSliceRows - 1) / kSliceRows * kSliceRows;
+  Geometry& g = pl->g;
+  g.N = N; g.C = C; g.H = H; g.W = W; g.K = K; g.pad = pad;
+  g.Ho = (int)Ho; g.Wo = (int)Wo; g.th = (int)th; g.tw = (int)tw; g.tpi = (int)(th * tw);
+  g.T = (int)T;
+  g.Tp = (int)((T + 127) / 128 * 128);
+  pl->n_tau_blocks = (g.T + pl->tb - 1) / pl->tb;
+  *out = pl;
+  return SWCONV_OK;
+}
+
+void swconv_plan_destroy(swconv_plan* pl) {
+  if (!pl) return;
+  void* bufs[] = {pl->dV, pl->dM, pl->d_stream, pl->d_slices, pl->d_sorted_rows, pl->d_items, pl->d_wdense};
+  for (void* b : bufs)
+    if (b) (void)hipFree(b);
+  delete pl;
+}
+
+int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, const float* vals) {
+  if (!pl) return SWCONV_EINVAL;
+  int rc = validate_csr(pl, rowptr, colidx, vals);
+  if (rc) return rc;
+  try {
+    pack_weights(pl, rowptr, colidx, vals);
+  } catch (const std::bad_alloc&) {
+    pl->have_sparse = false;
+    pl->sparse_on_device = false;
+    return SWCONV_ENOMEM;
+  }
+  return upload_sparse(pl);
+}
+
+int swconv_forward(swconv_plan* pl, void* hip_stream, const float* in_dev, float* out_dev) {
+  if (!pl || !in_dev || !out_dev) return SWCONV_EINVAL;
+  if (!pl->sparse_on_device) return SWCONV_ESTATE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  for (int stage = 0; stage < 3; ++stage) {
+    int rc = launch_stage(pl, st, stage, in_dev, out_dev);
+    if (rc) return rc;
+  }
+  pl->ran_forward = true;
+  return SWCONV_OK;
+}
+
+int swconv_profile_forward(swconv_plan* pl, void* hip_stream, const float* in_dev, float* out_dev, int iters,
+                           float* stage_ms) {
+  if (!pl || !in_dev || !out_dev || !stage_ms || iters < 1) return SWCONV_EINVAL;
+  if (!pl->sparse_on_device) return SWCONV_ESTATE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  std::vector<hipEvent_t> ev((size_t)iters * 4, nullptr);
+  int rc = SWCONV_OK;
+  for (auto& e : ev)
+    if (hipEventCreate(&e) != hipSuccess) rc = SWCONV_EHIP;
+  for (int it = 0; it < iters && !rc; ++it) {
+    hipEvent_t* e = &ev[(size_t)it * 4];
+    if (hipEventRecord(e[0], st) != hipSuccess) rc = SWCONV_EHIP;
+    for (int stage = 0; stage < 3 && !rc; ++stage) {
+      rc = launch_stage(pl, st, stage, in_dev, out_dev);
+      if (!rc && hipEventRecord(e[stage + 1], st) != hipSuccess) rc = SWCONV_EHIP;
+    }
+  }
+  if (hipStreamSynchronize(st) != hipSuccess) rc = rc ? rc : SWCONV_EHIP;
+  if (!rc) {
+    double sum[3] = {0, 0, 0};
+    for (int it = 0; it < iters && !rc; ++it)
+      for (int stage = 0; stage < 3; ++stage) {
+        float ms = 0;
+        if (hipEventElapsedTime(&ms, ev[(size_t)it * 4 + stage], ev[(size_t)it * 4 + stage + 1]) != hipSuccess) {
+          rc = SWCONV_EHIP;
+          break;
+        }
+        sum[stage] += ms;
+      }
+    if (!rc)
+      for (int stage = 0; stage < 3; ++stage) stage_ms[stage] = (float)(sum[stage] / iters);
+    pl->ran_forward = true;
+  }
+  for (auto& e : ev)
+    if (e) (void)hipEventDestroy(e);
+  if (rc) (void)hipGetLastError();
+  return rc;
+}
+
+int swconv_debug_copy_V(swconv_plan* pl, float* V_host) {
+  if (!pl || !V_host) return SWCONV_EINVAL;
+  if (!pl->ran_forward) return SWCONV_ESTATE;
+  return copy_padded_to_host(pl->dV, V_host, (size_t)pl->P * pl->g.C, pl->g.T, pl->g.Tp);
+}
+
+int swconv_debug_copy_M(swconv_plan* pl, float* M_host) {
+  if (!pl || !M_host) return SWCONV_EINVAL;
+  if (!pl->ran_forward) return SWCONV_ESTATE;
+  return copy_padded_to_host(pl->dM, M_host, (size_t)pl->P * pl->g.K, pl->g.T, pl->g.Tp);
+}
+
+int swconv_debug_export_weights(swconv_plan* pl, int32_t* rowptr, int32_t* colidx, float* vals) {
+  if (!pl || !rowptr) return SWCONV_EINVAL;
+  if (!pl->have_sparse) return SWCONV_ESTATE;
+  if (pl->nnz > 0 && (!colidx || !vals)) return SWCONV_EINVAL;
+  const int P = pl->P, K = pl->g.K, Kp = pl->Kp;
+  // row lengths back in original order -> rowptr
+  rowptr[0] = 0;
+  std::vector<int32_t> len((size_t)P * K, 0);
+  for (int p = 0; p < P; ++p)
+    for (int i = 0; i < Kp; ++i) {
+      const int k = pl->sorted_rows[(size_t)p * Kp + i];
+      if (k >= 0) len[(size_t)p * K + k] = pl->sorted_len[(size_t)p * Kp + i];
+    }
+  for (int64_t i = 0; i < (int64_t)P * K; ++i) rowptr[i + 1] = rowptr[i] + len[i];
+  for (const Slice& sl : pl->slices)
+    for (int r = 0; r < kSliceRows; ++r) {
+      const int k = pl->sorted_rows[sl.row0 + r];
+      if (k < 0) continue;
+      const int32_t q0 = rowptr[(int64_t)sl.p * K + k];
+      for (int32_t e = 0; e < pl->sorted_len[sl.row0 + r]; ++e) {
+        const uint32_t* slot = pl->stream.data() + ((size_t)sl.slot0 + e) * 8;
+        colidx[q0 + e] = (int32_t)slot[r];
+        std::memcpy(&vals[q0 + e], &slot[4 + r], sizeof(float));
+      }
+    }
+  return SWCONV_OK;
+}
+
+int swconv_plan_sizes(const swconv_plan* pl, int* P, int64_t* T, int* Ho, int* Wo) {
+  if (!pl) return SWCONV_EINVAL;
+  if (P) *P = pl->P;
+  if (T) *T = pl->g.T;
+  if (Ho) *Ho = pl->g.Ho;
+  if (Wo) *Wo = pl->g.Wo;
+  return SWCONV_OK;
+}
+
+int swconv_plan_weight_stats(const swconv_plan* pl, int64_t* nnz, int64_t* padded_nnz, int* work_items,
+                             int64_t* max_item) {
+  if (!pl) return SWCONV_EINVAL;
+  if (!pl->have_sparse) return SWCONV_ESTATE;
+  if (nnz) *nnz = pl->nnz;
+  if (padded_nnz) *padded_nnz = pl->padded_nnz;
+  if (work_items) *work_items = (int)pl->items.size();
+  if (max_item) *max_item = pl->max_item;
+  return SWCONV_OK;
+}
+
+int swconv_set_weights_dense(swconv_plan* pl, const float* wf) {
+  if (!pl || !wf) return SWCONV_EINVAL;
+  int rc = ensure_workspace(pl);
+  if (rc) return rc;
+  pl->dense_on_device = false;
+  // transpose to [P][C][Kq], output channels fastest, zero padded to the GEMM's row tile
+  const int P = pl->P, K = pl->g.K, C = pl->g.C;
+  const int Kq = (K + kDenseTileM - 1) / kDenseTileM * kDenseTileM;
+  std::vector<float> wt;
+  try {
+    wt.assign((size_t)P * C * Kq, 0.0f);
+  } catch (const std::bad_alloc&) {
+    return SWCONV_ENOMEM;
+  }
+  for (int p = 0; p < P; ++p)
+    for (int k = 0; k < K; ++k)
+      for (int c = 0; c < C; ++c) wt[((size_t)p * C + c) * Kq + k] = wf[((size_t)p * K + k) * C + c];
+  if ((rc = upload(&pl->d_wdense, wt))) return rc;
+  pl->Kq = Kq;
+  pl->dense_on_device = true;
+  return SWCONV_OK;
+}
+
+int swconv_forward_dense(swconv_plan* pl, void* hip_stream, const float* in_dev, float* out_dev) {
+  if (!pl || !in_dev || !out_dev) return SWCONV_EINVAL;
+  if (!pl->dense_on_device) return SWCONV_ESTATE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  int rc = launch_stage(pl, st, 0, in_dev, out_dev);
+  if (rc) return rc;
+  {
+    const Geometry& g = pl->g;
+    dim3 grid((g.Tp + kDenseTileN - 1) / kDenseTileN, (g.K + kDenseTileM - 1) / kDenseTileM, pl->P);
+    hipLaunchKernelGGL(dense_position_gemm_kernel, grid, dim3(256), 0, st, pl->d_wdense, pl->dV, pl->dM, g.K,
+                       pl->Kq, g.C, g.Tp);
+    HIP_TRY(hipGetLastError());
+  }
+  rc = launch_stage(pl, st, 2, in_dev, out_dev);
+  if (rc) return rc;
+  pl->ran_forward = true;
+  return SWCONV_OK;
+}
+
+}  // extern "C"
