@@ -18,7 +18,6 @@ using namespace swconv;
 
 namespace {
 
-constexpr int kSpmmWaves = 8;       // waves per SpMM workgroup
 constexpr int kMaxLdsBytes = 160 * 1024;
 constexpr int kSliceOverhead = 6;   // cost of starting/finishing a slice, in slots
 
@@ -58,6 +57,7 @@ struct swconv_plan {
   int m = 0, r = 0, t = 0, P = 0;
   int tpl = 1;   // tiles per lane in the sparse product
   int tb = 64;   // tile block = 64 * tpl
+  int waves = 8; // waves per workgroup in the sparse product
   int Kp = 0;    // K rounded up to a multiple of the slice height
   int Kq = 0;    // K rounded up to the dense GEMM's row tile
   int n_tau_blocks = 0;
@@ -101,7 +101,14 @@ int ensure_workspace(swconv_plan* pl) {
 template <int M>
 int launch_input_transform(const swconv_plan* pl, hipStream_t st, const float* in) {
   dim3 grid(pl->g.Tp / 64, (pl->g.C + 3) / 4);
-  hipLaunchKernelGGL(input_transform_kernel<M>, grid, dim3(256), 0, st, in, pl->dV, pl->g);
+  const size_t lds = (size_t)4 * pl->g.slots * pl->g.in_span * sizeof(float);
+  auto kern = input_transform_kernel<M>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, in, pl->dV, pl->g);
   HIP_TRY(hipGetLastError());
   return SWCONV_OK;
 }
@@ -109,30 +116,38 @@ int launch_input_transform(const swconv_plan* pl, hipStream_t st, const float* i
 template <int M>
 int launch_output_transform(const swconv_plan* pl, hipStream_t st, float* out) {
   dim3 grid(pl->g.Tp / 64, (pl->g.K + 3) / 4);
-  hipLaunchKernelGGL(output_transform_kernel<M>, grid, dim3(256), 0, st, pl->dM, out, pl->g);
-  HIP_TRY(hipGetLastError());
-  return SWCONV_OK;
-}
-
-template <int TPL>
-int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
-  const int n_items = (int)pl->items.size();
-  if (n_items == 0) return SWCONV_OK;
-  const size_t lds = (size_t)pl->g.C * 64 * TPL * sizeof(float);
-  auto kern = spmm_kernel<TPL, kSpmmWaves>;
+  const size_t lds = (size_t)4 * pl->g.slots * pl->g.out_span * sizeof(float);
+  auto kern = output_transform_kernel<M>;
   static bool attr_set = false;
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(n_items), dim3(kSpmmWaves * 64), lds, st, pl->dV, pl->dM, pl->d_stream,
-                     pl->d_slices, pl->d_sorted_rows, pl->d_items, n_items, pl->g.C, pl->g.K, pl->g.Tp);
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, pl->dM, out, pl->g);
+  HIP_TRY(hipGetLastError());
+  return SWCONV_OK;
+}
+
+template <int TPL, int NW>
+int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
+  const int n_items = (int)pl->items.size();
+  if (n_items == 0) return SWCONV_OK;
+  const size_t lds = (size_t)pl->g.C * 64 * TPL * sizeof(float);
+  auto kern = spmm_kernel<TPL, NW>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(n_items), dim3(NW * 64), lds, st, pl->dV, pl->dM, pl->d_stream, pl->d_slices,
+                     pl->d_sorted_rows, pl->d_items, n_items, pl->g.C, pl->g.K, pl->g.Tp);
   HIP_TRY(hipGetLastError());
   return SWCONV_OK;
 }
 
 int launch_spmm(const swconv_plan* pl, hipStream_t st) {
-  return pl->tpl == 2 ? launch_spmm_t<2>(pl, st) : launch_spmm_t<1>(pl, st);
+  if (pl->tpl == 2) return pl->waves == 16 ? launch_spmm_t<2, 16>(pl, st) : launch_spmm_t<2, 8>(pl, st);
+  return pl->waves == 16 ? launch_spmm_t<1, 16>(pl, st) : launch_spmm_t<1, 8>(pl, st);
 }
 
 int launch_stage(const swconv_plan* pl, hipStream_t st, int stage, const float* in, float* out) {
@@ -188,14 +203,17 @@ void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx,
       Slice& sl = pl->slices[(size_t)p * slices_per_pos + s];
       sl.p = p;
       sl.row0 = p * Kp + s * kSliceRows;
-      sl.len = pl->sorted_len[sl.row0];  // rows are sorted: the first is the longest
+      // rows are sorted: the first is the longest; round up to whole scalar fetches
+      sl.len = (pl->sorted_len[sl.row0] + kSlotUnroll - 1) / kSlotUnroll * kSlotUnroll;
       sl.slot0 = (uint32_t)slot_cursor;
       slot_cursor += sl.len;
       pos_cost[p] += sl.len + kSliceOverhead;
     }
   }
   pl->padded_nnz = (int64_t)slot_cursor * kSliceRows;
-  pl->stream.assign((size_t)slot_cursor * 8, 0u);  // column 0, weight +0.0f
+  // padding = column 0, weight +0.0f; one spare batch at the end keeps the kernel's whole-batch
+  // fetches in bounds
+  pl->stream.assign(((size_t)slot_cursor + kBatchSlots) * 8, 0u);
   for (size_t s = 0; s < pl->slices.size(); ++s) {
     const Slice& sl = pl->slices[s];
     const int32_t* rp = rowptr + (int64_t)sl.p * K;
@@ -217,7 +235,7 @@ void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx,
   // the panels and the weights of the few positions it works on).
   const int64_t total_cost = std::accumulate(pos_cost.begin(), pos_cost.end(), (int64_t)0);
   const int target_wgs = env_int("SWCONV_SPMM_TARGET_WGS", 1024);
-  const int min_slices_per_wg = std::max(1, env_int("SWCONV_SPMM_MIN_SLICES", kSpmmWaves));
+  const int min_slices_per_wg = std::max(1, env_int("SWCONV_SPMM_MIN_SLICES", pl->waves));
   const int64_t target_items = std::max<int64_t>(P, (target_wgs + pl->n_tau_blocks - 1) / pl->n_tau_blocks);
   const int64_t cost_per_item = std::max<int64_t>(1, (total_cost + target_items - 1) / target_items);
   pl->items.clear();
@@ -304,6 +322,7 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   pl->t = t;
   pl->P = P;
   pl->tpl = tpl;
+  pl->waves = env_int("SWCONV_SPMM_WAVES", 8) == 16 ? 16 : 8;
   pl->tb = 64 * tpl;
   pl->Kp = (K + kSliceRows - 1) / kSliceRows * kSliceRows;
   Geometry& g = pl->g;
@@ -311,6 +330,15 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   g.Ho = (int)Ho; g.Wo = (int)Wo; g.th = (int)th; g.tw = (int)tw; g.tpi = (int)(th * tw);
   g.T = (int)T;
   g.Tp = (int)((T + 127) / 128 * 128);
+  // LDS staging bounds of the transform kernels for any run of 64 consecutive tiles
+  const int rows_t = (int)std::min<int64_t>(th, (64 + tw - 2) / tw + 1);
+  g.slots = (int)std::min<int64_t>(N, (64 + g.tpi - 2) / g.tpi + 1);
+  g.in_span = std::min(H, rows_t * m + t - m) * W;
+  g.out_span = std::min(g.Ho, rows_t * m) * g.Wo;
+  if ((int64_t)4 * g.slots * std::max(g.in_span, g.out_span) * (int64_t)sizeof(float) > kMaxLdsBytes) {
+    delete pl;
+    return SWCONV_EUNSUPPORTED;
+  }
   pl->n_tau_blocks = (g.T + pl->tb - 1) / pl->tb;
   *out = pl;
   return SWCONV_OK;
