@@ -82,7 +82,7 @@ void swconv_plan_destroy(swconv_plan* plan);
  *           legal and are treated as non-zeros.  nnz = 0 is legal (colidx/vals may be NULL).
  * The arrays are validated, re-packed into the kernels' sliced layout (rows of a position
  * sorted by length, grouped four at a time, padded with zero weights) together with a
- * load-balanced work list, and copied to the device before the call returns; the caller keeps
+ * static, cost-balanced schedule for the persistent workgroups of the sparse product, and copied to the device before the call returns; the caller keeps
  * ownership of its arrays.  May be called again with a new pattern.  Blocks the host.
  * Errors: EINVAL on any CSR violation (the plan keeps its previous weights); ENOMEM; EHIP when
  * no device is usable - the host-side packed copy is still kept in that case, so
@@ -150,8 +150,8 @@ int swconv_plan_sizes(const swconv_plan* plan, int* P, int64_t* T, int* Ho, int*
  * Statistics of the packed weights and the work list built by swconv_set_weights:
  *   nnz          stored entries as passed in
  *   padded_nnz   entries after padding to the sliced layout (what the kernel multiplies)
- *   work_items   entries of the load-balanced work list (per tile block)
- *   max_item     padded entries in the heaviest work item
+ *   work_items   entries of the statically scheduled work list
+ *   max_item     padded entries multiplied by the heaviest persistent workgroup
  * Errors: ESTATE when no sparse weights were set.
  */
 int swconv_plan_weight_stats(const swconv_plan* plan, int64_t* nnz, int64_t* padded_nnz, int* work_items,

@@ -69,15 +69,18 @@ struct swconv_plan {
   std::vector<Slice> slices;         // P * Kp/4
   std::vector<int32_t> sorted_rows;  // P * Kp: original row k of each sorted row, -1 = padding
   std::vector<int32_t> sorted_len;   // P * Kp: stored entries of each sorted row
-  std::vector<WorkItem> items;
+  std::vector<WorkItem> items;       // grouped by workgroup
+  std::vector<int32_t> wg_begin;     // n_wgs_used + 1 offsets into items
+  int n_wgs = 512;                   // persistent workgroups the device can hold at once
+  int n_wgs_used = 0;                // workgroups the current schedule uses
 
   // device
   bool on_device = false, sparse_on_device = false, dense_on_device = false, ran_forward = false;
   float *dV = nullptr, *dM = nullptr;
   uint32_t* d_stream = nullptr;
   Slice* d_slices = nullptr;
-  int32_t* d_sorted_rows = nullptr;
   WorkItem* d_items = nullptr;
+  int32_t* d_wg_begin = nullptr;
   float* d_wdense = nullptr;  // [P][C][Kq]
 };
 
@@ -130,17 +133,16 @@ int launch_output_transform(const swconv_plan* pl, hipStream_t st, float* out) {
 
 template <int TPL, int NW>
 int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
-  const int n_items = (int)pl->items.size();
-  if (n_items == 0) return SWCONV_OK;
-  const size_t lds = (size_t)pl->g.C * 64 * TPL * sizeof(float);
+  if (pl->n_wgs_used == 0) return SWCONV_OK;
+  const size_t lds = (size_t)pl->g.C * pl->tb * sizeof(float);
   auto kern = spmm_kernel<TPL, NW>;
   static bool attr_set = false;
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(n_items), dim3(NW * 64), lds, st, pl->dV, pl->dM, pl->d_stream, pl->d_slices,
-                     pl->d_sorted_rows, pl->d_items, n_items, pl->g.C, pl->g.K, pl->g.Tp);
+  hipLaunchKernelGGL(kern, dim3(pl->n_wgs_used), dim3(NW * 64), lds, st, pl->dV, pl->dM, pl->d_stream, pl->d_slices,
+                     (int)pl->slices.size(), pl->d_items, pl->d_wg_begin, pl->g.C, pl->g.K, pl->g.Tp, pl->tb);
   HIP_TRY(hipGetLastError());
   return SWCONV_OK;
 }
@@ -178,6 +180,89 @@ int validate_csr(const swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   return SWCONV_OK;
 }
 
+// Static schedule of the sparse product.  Each position is cut into strided slice subsets
+// ("chunks", as many as its cost warrants, so item costs are alike whatever the per-position
+// densities are); one work item = (position, tile block, chunk).  Panels (position, tile block)
+// are dealt to the 8 XCDs, heaviest first to the least loaded XCD, so that all items of a panel
+// share one L2; inside an XCD the items go, heaviest first, to the least loaded of that XCD's
+// persistent workgroups (workgroup b runs on XCD b % 8).  Every workgroup then walks its own
+// list, sorted by panel so that a panel already in LDS is reused.
+void build_schedule(swconv_plan* pl, const std::vector<int64_t>& pos_cost) {
+  const int P = pl->P, slices_per_pos = pl->Kp / kSliceRows, ntb = pl->n_tau_blocks;
+  const int64_t panel_cost = (int64_t)env_int("SWCONV_SPMM_PANEL_COST", 40) * pl->waves;
+  const int64_t total_cost = std::accumulate(pos_cost.begin(), pos_cost.end(), (int64_t)0) * ntb;
+  const int wgs_max = std::max(1, pl->n_wgs);
+  const int items_per_wg = std::max(1, env_int("SWCONV_SPMM_ITEMS_PER_WG", 2));
+  const int64_t cost_per_item = std::max<int64_t>(1, total_cost / ((int64_t)wgs_max * items_per_wg));
+
+  struct Item { WorkItem w; int64_t cost; int64_t slots; int panel; };
+  std::vector<Item> all;
+  std::vector<int64_t> panel_total((size_t)P * ntb, 0);
+  for (int p = 0; p < P; ++p) {
+    int chunks = (int)((pos_cost[p] + cost_per_item - 1) / cost_per_item);
+    chunks = std::max(1, std::min(chunks, std::max(1, slices_per_pos / pl->waves)));
+    const int s0 = p * slices_per_pos, s1 = s0 + slices_per_pos;
+    for (int ch = 0; ch < chunks; ++ch) {
+      int64_t slots = 0, cost = panel_cost;
+      for (int s = s0 + ch; s < s1; s += chunks) {
+        slots += pl->slices[s].len;
+        cost += pl->slices[s].len + kSliceOverhead;
+      }
+      for (int tb = 0; tb < ntb; ++tb) {
+        all.push_back(Item{WorkItem{p, tb, s0 + ch, s1, chunks, {0, 0, 0}}, cost, slots, p * ntb + tb});
+        panel_total[(size_t)p * ntb + tb] += cost;
+      }
+    }
+  }
+  const int n_wgs = (int)std::min<size_t>(wgs_max, all.size());
+  pl->n_wgs_used = n_wgs;
+
+  // panels -> XCDs (only XCDs that own at least one workgroup), normalised by workgroup count
+  int xcd_wgs[kXcds];
+  for (int x = 0; x < kXcds; ++x) xcd_wgs[x] = n_wgs / kXcds + (x < n_wgs % kXcds ? 1 : 0);
+  std::vector<int> porder(panel_total.size());
+  std::iota(porder.begin(), porder.end(), 0);
+  std::stable_sort(porder.begin(), porder.end(), [&](int a, int b) { return panel_total[a] > panel_total[b]; });
+  std::vector<int> panel_xcd(panel_total.size(), 0);
+  int64_t xcd_load[kXcds] = {0};
+  for (int pi : porder) {
+    int best = -1;
+    for (int x = 0; x < kXcds; ++x) {
+      if (xcd_wgs[x] == 0) continue;
+      // compare load per workgroup: load[x] / wgs[x] < load[best] / wgs[best]
+      if (best < 0 || xcd_load[x] * xcd_wgs[best] < xcd_load[best] * xcd_wgs[x]) best = x;
+    }
+    panel_xcd[pi] = best;
+    xcd_load[best] += panel_total[pi];
+  }
+
+  // items -> workgroups of the panel's XCD
+  std::vector<int> iorder(all.size());
+  std::iota(iorder.begin(), iorder.end(), 0);
+  std::stable_sort(iorder.begin(), iorder.end(), [&](int a, int b) { return all[a].cost > all[b].cost; });
+  std::vector<int64_t> wg_load(n_wgs, 0), wg_slots(n_wgs, 0);
+  std::vector<std::vector<int>> wg_items(n_wgs);
+  for (int ii : iorder) {
+    const int x = panel_xcd[all[ii].panel];
+    int best = -1;
+    for (int b = x; b < n_wgs; b += kXcds)
+      if (best < 0 || wg_load[b] < wg_load[best]) best = b;
+    wg_items[best].push_back(ii);
+    wg_load[best] += all[ii].cost;
+    wg_slots[best] += all[ii].slots;
+  }
+  pl->items.clear();
+  pl->wg_begin.assign((size_t)n_wgs + 1, 0);
+  pl->max_item = 0;
+  for (int b = 0; b < n_wgs; ++b) {
+    std::stable_sort(wg_items[b].begin(), wg_items[b].end(),
+                     [&](int a, int c) { return all[a].panel < all[c].panel; });
+    for (int ii : wg_items[b]) pl->items.push_back(all[ii].w);
+    pl->wg_begin[b + 1] = (int32_t)pl->items.size();
+    pl->max_item = std::max(pl->max_item, wg_slots[b] * kSliceRows);
+  }
+}
+
 // Re-pack per-position CSR into the sliced layout and build the work list.
 void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, const float* vals) {
   const int P = pl->P, K = pl->g.K, Kp = pl->Kp;
@@ -206,13 +291,15 @@ void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx,
       // rows are sorted: the first is the longest; round up to whole scalar fetches
       sl.len = (pl->sorted_len[sl.row0] + kSlotUnroll - 1) / kSlotUnroll * kSlotUnroll;
       sl.slot0 = (uint32_t)slot_cursor;
+      for (int r = 0; r < kSliceRows; ++r) sl.k[r] = pl->sorted_rows[sl.row0 + r];
       slot_cursor += sl.len;
       pos_cost[p] += sl.len + kSliceOverhead;
     }
   }
   pl->padded_nnz = (int64_t)slot_cursor * kSliceRows;
-  // padding = column 0, weight +0.0f; one spare batch at the end keeps the kernel's whole-batch
-  // fetches in bounds
+  // a slot entry is (byte offset of the panel row of column c, weight); padding = row 0,
+  // weight +0.0f; one spare batch at the end keeps the kernel's whole-batch fetches in bounds
+  const uint32_t row_bytes = (uint32_t)pl->tb * sizeof(float);
   pl->stream.assign(((size_t)slot_cursor + kBatchSlots) * 8, 0u);
   for (size_t s = 0; s < pl->slices.size(); ++s) {
     const Slice& sl = pl->slices[s];
@@ -223,36 +310,13 @@ void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx,
       const int32_t q0 = rp[k], len = rp[k + 1] - rp[k];
       for (int32_t e = 0; e < len; ++e) {
         uint32_t* slot = pl->stream.data() + ((size_t)sl.slot0 + e) * 8;
-        slot[r] = (uint32_t)colidx[q0 + e];
+        slot[r] = (uint32_t)colidx[q0 + e] * row_bytes;
         std::memcpy(&slot[4 + r], &vals[q0 + e], sizeof(float));
       }
     }
   }
 
-  // Work list.  Each position is cut into a number of strided slice subsets proportional to
-  // its cost, so that all workgroups carry about the same number of slots whatever the
-  // per-position densities are; positions stay contiguous in the list (one XCD's L2 then holds
-  // the panels and the weights of the few positions it works on).
-  const int64_t total_cost = std::accumulate(pos_cost.begin(), pos_cost.end(), (int64_t)0);
-  const int target_wgs = env_int("SWCONV_SPMM_TARGET_WGS", 1024);
-  const int min_slices_per_wg = std::max(1, env_int("SWCONV_SPMM_MIN_SLICES", pl->waves));
-  const int64_t target_items = std::max<int64_t>(P, (target_wgs + pl->n_tau_blocks - 1) / pl->n_tau_blocks);
-  const int64_t cost_per_item = std::max<int64_t>(1, (total_cost + target_items - 1) / target_items);
-  pl->items.clear();
-  pl->max_item = 0;
-  for (int p = 0; p < P; ++p) {
-    int chunks = (int)((pos_cost[p] + cost_per_item - 1) / cost_per_item);
-    chunks = std::max(1, std::min(chunks, std::max(1, slices_per_pos / min_slices_per_wg)));
-    const int s0 = p * slices_per_pos, s1 = s0 + slices_per_pos;
-    for (int tb = 0; tb < pl->n_tau_blocks; ++tb) {
-      for (int ch = 0; ch < chunks; ++ch) {
-        pl->items.push_back(WorkItem{p, tb, s0 + ch, s1, chunks});
-        int64_t slots = 0;
-        for (int s = s0 + ch; s < s1; s += chunks) slots += pl->slices[s].len;
-        pl->max_item = std::max(pl->max_item, slots * kSliceRows);
-      }
-    }
-  }
+  build_schedule(pl, pos_cost);
   pl->have_sparse = true;
 }
 
@@ -262,8 +326,8 @@ int upload_sparse(swconv_plan* pl) {
   pl->sparse_on_device = false;
   if ((rc = upload(&pl->d_stream, pl->stream))) return rc;
   if ((rc = upload(&pl->d_slices, pl->slices))) return rc;
-  if ((rc = upload(&pl->d_sorted_rows, pl->sorted_rows))) return rc;
   if ((rc = upload(&pl->d_items, pl->items))) return rc;
+  if ((rc = upload(&pl->d_wg_begin, pl->wg_begin))) return rc;
   HIP_TRY(hipDeviceSynchronize());
   pl->sparse_on_device = true;
   return SWCONV_OK;
@@ -303,17 +367,22 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   const int64_t T = (int64_t)N * th * tw;
   const int64_t lim = (int64_t)1 << 31;
   // every flat index the kernels form in 32 bits, and the CSR offsets, must fit int32
-  if (T + 128 >= lim || (int64_t)P * K * C >= lim || (int64_t)H * W >= lim || Ho * Wo >= lim ||
+  if (T + 256 >= lim || (int64_t)P * K * C >= lim || (int64_t)H * W >= lim || Ho * Wo >= lim ||
       (int64_t)N * C * H * W >= ((int64_t)1 << 40) || (int64_t)P * (K + 4) >= lim)
     return SWCONV_EINVAL;
 
   swconv_plan* pl = new (std::nothrow) swconv_plan();
   if (!pl) return SWCONV_ENOMEM;
-  // tile block: two tiles per lane when the C x 128 panel still lets two workgroups share a CU
-  int tpl = env_int("SWCONV_SPMM_TPL", 0);
-  if (tpl != 1 && tpl != 2) tpl = 1;
-  if ((int64_t)C * 64 * tpl * (int64_t)sizeof(float) > kMaxLdsBytes) tpl = 1;
-  if ((int64_t)C * 64 * (int64_t)sizeof(float) > kMaxLdsBytes) {
+  // Tile block of the sparse product.  Two tiles per lane (one 8-byte LDS read feeds two FMAs)
+  // with the largest block TB <= 128, TB % 8 == 0, whose C x TB panel fits LDS - if that keeps
+  // more than 32 lanes busy; else one tile per lane with TB = 64.
+  int tpl = 2, tb = (int)std::min<int64_t>(128, kMaxLdsBytes / ((int64_t)C * (int64_t)sizeof(float)) / 8 * 8);
+  const int force_tpl = env_int("SWCONV_SPMM_TPL", 0);
+  if (tb <= 64 || force_tpl == 1) {
+    tpl = 1;
+    tb = 64;
+  }
+  if ((int64_t)C * tb * (int64_t)sizeof(float) > kMaxLdsBytes) {
     delete pl;
     return SWCONV_EUNSUPPORTED;
   }
@@ -322,14 +391,18 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   pl->t = t;
   pl->P = P;
   pl->tpl = tpl;
-  pl->waves = env_int("SWCONV_SPMM_WAVES", 8) == 16 ? 16 : 8;
-  pl->tb = 64 * tpl;
+  // one workgroup per CU when the panel takes more than half of LDS: then 16 waves, else 8
+  const int dflt_waves = (int64_t)C * tb * (int64_t)sizeof(float) * 2 > kMaxLdsBytes ? 16 : 8;
+  pl->waves = env_int("SWCONV_SPMM_WAVES", dflt_waves) == 16 ? 16 : 8;
+  pl->tb = tb;
   pl->Kp = (K + kSliceRows - 1) / kSliceRows * kSliceRows;
   Geometry& g = pl->g;
   g.N = N; g.C = C; g.H = H; g.W = W; g.K = K; g.pad = pad;
   g.Ho = (int)Ho; g.Wo = (int)Wo; g.th = (int)th; g.tw = (int)tw; g.tpi = (int)(th * tw);
   g.T = (int)T;
-  g.Tp = (int)((T + 127) / 128 * 128);
+  // row pitch of V and M: whole tile blocks of the sparse product, and a multiple of 128 for the
+  // transform kernels (64-tile blocks) and the dense comparison GEMM (128-tile blocks)
+  g.Tp = (int)(((T + tb - 1) / tb * tb + 127) / 128 * 128);
   // LDS staging bounds of the transform kernels for any run of 64 consecutive tiles
   const int rows_t = (int)std::min<int64_t>(th, (64 + tw - 2) / tw + 1);
   g.slots = (int)std::min<int64_t>(N, (64 + g.tpi - 2) / g.tpi + 1);
@@ -346,7 +419,7 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
 
 void swconv_plan_destroy(swconv_plan* pl) {
   if (!pl) return;
-  void* bufs[] = {pl->dV, pl->dM, pl->d_stream, pl->d_slices, pl->d_sorted_rows, pl->d_items, pl->d_wdense};
+  void* bufs[] = {pl->dV, pl->dM, pl->d_stream, pl->d_slices, pl->d_items, pl->d_wg_begin, pl->d_wdense};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
   delete pl;
@@ -356,6 +429,19 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   if (!pl) return SWCONV_EINVAL;
   int rc = validate_csr(pl, rowptr, colidx, vals);
   if (rc) return rc;
+  {
+    // persistent workgroups the device holds at once: as many per CU as the panel's LDS allows
+    int cus = 256, ndev = 0, dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0 && hipGetDevice(&dev) == hipSuccess &&
+        hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+      cus = prop.multiProcessorCount;
+    else
+      (void)hipGetLastError();
+    const size_t panel_bytes = (size_t)pl->g.C * pl->tb * sizeof(float);
+    const int per_cu = std::max<int>(1, std::min<int>(32 / pl->waves, (int)(kMaxLdsBytes / panel_bytes)));
+    pl->n_wgs = std::max(1, env_int("SWCONV_SPMM_WGS", cus * per_cu));
+  }
   try {
     pack_weights(pl, rowptr, colidx, vals);
   } catch (const std::bad_alloc&) {
@@ -450,7 +536,7 @@ int swconv_debug_export_weights(swconv_plan* pl, int32_t* rowptr, int32_t* colid
       const int32_t q0 = rowptr[(int64_t)sl.p * K + k];
       for (int32_t e = 0; e < pl->sorted_len[sl.row0 + r]; ++e) {
         const uint32_t* slot = pl->stream.data() + ((size_t)sl.slot0 + e) * 8;
-        colidx[q0 + e] = (int32_t)slot[r];
+        colidx[q0 + e] = (int32_t)(slot[r] / ((uint32_t)pl->tb * sizeof(float)));
         std::memcpy(&vals[q0 + e], &slot[4 + r], sizeof(float));
       }
     }

@@ -8,7 +8,7 @@
 //   M    [P][K][Tp]              per-position products
 //   out  [N][K][Ho][Wo]
 // Lanes of a wavefront map to consecutive tiles tau everywhere, so every V/M access of a wave
-// is one contiguous 256-byte (or 512-byte) segment.
+// is one contiguous 256-byte segment.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -43,22 +43,25 @@ __device__ __forceinline__ ImagePart image_part(const Geometry& g, int n, int ta
   return ip;
 }
 
-// One slice = four rows of one position's sparse matrix, rows sorted by length.
+// One slice = four rows of one position's sparse matrix, rows sorted by length.  32 bytes, so a
+// wave fetches a whole descriptor with one scalar load.
 struct Slice {
   uint32_t slot0;  // first slot of the slice in the packed stream (8 dwords per slot)
-  int32_t len;     // slots in the slice = length of its longest row
-  int32_t row0;    // index of its first row in the sorted-row table (P * Kp entries)
+  int32_t len;     // slots in the slice = length of its longest row, rounded up to kSlotUnroll
+  int32_t row0;    // index of its first row in the host's sorted-row table (P * Kp entries)
   int32_t p;       // position
+  int32_t k[4];    // output channel of each of the four rows, -1 = padding row
 };
 
-// One workgroup's share of the sparse product: a tile block of one position and a strided
-// subset of that position's slices.
+// One unit of the sparse product: a tile block of one position and a strided subset of that
+// position's slices.  32 bytes.
 struct WorkItem {
   int32_t p;
   int32_t tau_block;
   int32_t slice_begin;  // first slice taken
   int32_t slice_end;    // one past the position's last slice
   int32_t stride;       // distance between slices taken
+  int32_t pad[3];
 };
 
 constexpr int kSliceRows = 4;
@@ -153,110 +156,163 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
 
 // ---------------------------------------------------------------------------------------------
 // Step 2: M[p] = W_F[p] * V[p] on the plain fp32 ALUs.
-// A workgroup stages the C x TB panel V[p][:, tau_block] in LDS once (all its loads in flight
-// before the first LDS write); each wave then walks its slices.  A slice's stream is a sequence
-// of slots, each holding one (column, weight) pair for each of the slice's four rows; slices are
-// padded to an even number of slots.  Per batch of eight slots the wave fetches 64 dwords with
-// wave-uniform (scalar) loads, reads the 32 panel rows at lane-consecutive addresses and does
-// 32 FMAs per tile into four register accumulators (one per row).  TPL tiles per lane,
-// TB = 64 * TPL.
+//
+// Persistent workgroups: workgroup b walks the work items [wg_begin[b], wg_begin[b+1]) that the
+// host's static schedule gave it (equal cost per workgroup, items of one panel kept together and
+// on one XCD).  For an item it stages the C x TB panel V[p][:, tau_block] in LDS (unless the
+// previous item used the same panel), then each wave walks its share of the item's slices.
+//
+// A slice's stream is a sequence of slots, each holding one (panel row byte offset, weight) pair
+// for each of the slice's four rows.  Per batch of eight slots the wave fetches 64 dwords with
+// four back-to-back wave-uniform (scalar) loads; weights stay in scalar registers, there is one
+// vector accumulator per row and tile.
+//
+// LDS is the binding unit: a CU retires about one LDS instruction per 4-5 clocks whatever its
+// width up to 8 bytes per lane, so the kernel reads two tiles per lane with one 8-byte access
+// (TPL = 2, tile block TB <= 128 chosen so that the panel fits LDS) wherever that feeds more
+// FMAs per LDS instruction than one tile per lane does.  With TPL = 1 (TB = 64) the panel
+// operand is read with ds_read_addtid_b32, whose address is M0 + 4 * lane: the row offset goes
+// from its scalar register straight into M0 and no vector address arithmetic is spent.
 constexpr int kSlotUnroll = 2;   // slice lengths are multiples of this many slots
 constexpr int kBatchSlots = 8;   // slots fetched per scalar-memory round trip
+
+// Eight panel reads for eight wave-uniform row offsets.  One wait state is required between the
+// write of M0 and an LDS add-TID instruction (s_nop 0).  The loads are complete on return.
+__device__ __forceinline__ void panel_read8(const uint32_t (&off)[8], float (&x)[8]) {
+  asm volatile(
+      "s_mov_b32 m0, %8\n s_nop 0\n ds_read_addtid_b32 %0\n"
+      "s_mov_b32 m0, %9\n s_nop 0\n ds_read_addtid_b32 %1\n"
+      "s_mov_b32 m0, %10\n s_nop 0\n ds_read_addtid_b32 %2\n"
+      "s_mov_b32 m0, %11\n s_nop 0\n ds_read_addtid_b32 %3\n"
+      "s_mov_b32 m0, %12\n s_nop 0\n ds_read_addtid_b32 %4\n"
+      "s_mov_b32 m0, %13\n s_nop 0\n ds_read_addtid_b32 %5\n"
+      "s_mov_b32 m0, %14\n s_nop 0\n ds_read_addtid_b32 %6\n"
+      "s_mov_b32 m0, %15\n s_nop 0\n ds_read_addtid_b32 %7\n"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]), "=&v"(x[7])
+      : "s"(off[0]), "s"(off[1]), "s"(off[2]), "s"(off[3]), "s"(off[4]), "s"(off[5]), "s"(off[6]), "s"(off[7])
+      : "memory");
+}
 
 template <int TPL, int NWAVES>
 __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restrict__ V, float* __restrict__ Mbuf,
                                                            const uint32_t* __restrict__ stream,
-                                                           const Slice* __restrict__ slices,
-                                                           const int32_t* __restrict__ sorted_rows,
-                                                           const WorkItem* __restrict__ items, int n_items, int C,
-                                                           int K, int Tp) {
-  constexpr int TB = 64 * TPL;
+                                                           const Slice* __restrict__ slices, int n_slices,
+                                                           const WorkItem* __restrict__ items,
+                                                           const int32_t* __restrict__ wg_begin, int C, int K,
+                                                           int Tp, int TB) {
   constexpr int NT = NWAVES * 64;
-  extern __shared__ float panel[];  // [C][TB]
-  const int vid = xcd_contiguous_id(blockIdx.x, n_items);
-  const WorkItem it = items[vid];
+  extern __shared__ float panel[];  // [C][TB], at LDS offset 0 of the workgroup
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int tau0 = it.tau_block * TB;
+  const int item_begin = wg_begin[blockIdx.x], item_end = wg_begin[blockIdx.x + 1];
+  int cur_p = -1, cur_tb = -1;
+  // TPL = 2: lane l owns the adjacent tiles 2l, 2l+1 of the block and reads them with one 8-byte
+  // LDS access; when TB < 128 the lanes past TB/2 idle (they read lane 0's words, store nothing)
+  const bool lane_active = TPL == 1 || 2 * lane < TB;
+  const float* lane_panel = panel + (lane_active ? lane * TPL : 0);
 
-  {  // stage the panel: rows of TB floats, 16 bytes per lane, 4 loads in flight per lane
-    const float* src = V + ((size_t)it.p * C) * Tp + tau0;
-    constexpr int V4_PER_ROW = TB / 4;
-    constexpr int U = 4;
-    const int total = C * V4_PER_ROW;
-    int base = threadIdx.x;
-    for (; base + (U - 1) * NT < total; base += NT * U) {  // full batches, no bounds checks
-      float4 buf[U];
+  for (int item = item_begin; item < item_end; ++item) {
+    const WorkItem it = items[item];
+    const int tau0 = it.tau_block * TB;
+    if (it.p != cur_p || it.tau_block != cur_tb) {  // uniform for the workgroup
+      cur_p = it.p;
+      cur_tb = it.tau_block;
+      __syncthreads();  // every wave is done reading the previous panel
+      // stage the panel: rows of TB floats, 16 bytes per lane, all of a lane's loads in flight
+      // before its first LDS write
+      const float* src = V + ((size_t)it.p * C) * Tp + tau0;
+      const int V4_PER_ROW = TB / 4;
+      constexpr int U = 4;
+      const int total = C * V4_PER_ROW;
+      int base = threadIdx.x;
+      for (; base + (U - 1) * NT < total; base += NT * U) {  // full batches, no bounds checks
+        float4 buf[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int idx = base + u * NT;
-        const int row = idx / V4_PER_ROW, q = idx - row * V4_PER_ROW;
-        buf[u] = *reinterpret_cast<const float4*>(src + (size_t)row * Tp + q * 4);
+        for (int u = 0; u < U; ++u) {
+          const int idx = base + u * NT;
+          const int row = idx / V4_PER_ROW, q = idx - row * V4_PER_ROW;
+          buf[u] = *reinterpret_cast<const float4*>(src + (size_t)row * Tp + q * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) *reinterpret_cast<float4*>(panel + (base + u * NT) * 4) = buf[u];
       }
-#pragma unroll
-      for (int u = 0; u < U; ++u) *reinterpret_cast<float4*>(panel + (base + u * NT) * 4) = buf[u];
+      for (; base < total; base += NT) {
+        const int row = base / V4_PER_ROW, q = base - row * V4_PER_ROW;
+        *reinterpret_cast<float4*>(panel + base * 4) =
+            *reinterpret_cast<const float4*>(src + (size_t)row * Tp + q * 4);
+      }
+      __syncthreads();
     }
-    for (; base < total; base += NT) {
-      const int row = base / V4_PER_ROW, q = base - row * V4_PER_ROW;
-      *reinterpret_cast<float4*>(panel + base * 4) = *reinterpret_cast<const float4*>(src + (size_t)row * Tp + q * 4);
-    }
-  }
-  __syncthreads();
 
-  const float* lane_panel = panel + lane * TPL;
-  for (int s = it.slice_begin + wave * it.stride; s < it.slice_end; s += NWAVES * it.stride) {
-    const Slice sl = slices[s];
-    const uint32_t* sp = stream + (size_t)sl.slot0 * 8;
-    float acc[kSliceRows][TPL];
+    const int step = NWAVES * it.stride;
+    int s = it.slice_begin + wave * it.stride;
+    if (s >= it.slice_end) continue;
+    Slice sl = slices[s];
+    while (true) {
+      // descriptor of this wave's next slice, fetched while the current one is computed (the
+      // index is clamped, so the load is unconditional and in bounds)
+      const int s_next = s + step;
+      const Slice sl_next = slices[min(s_next, n_slices - 1)];
+      const uint32_t* sp = stream + (size_t)sl.slot0 * 8;
+      float acc[kSliceRows][TPL];
 #pragma unroll
-    for (int r = 0; r < kSliceRows; ++r)
+      for (int r = 0; r < kSliceRows; ++r)
 #pragma unroll
-      for (int e = 0; e < TPL; ++e) acc[r][e] = 0.0f;
-    // one batch = kBatchSlots slots = 64 dwords fetched with four back-to-back scalar loads, so
-    // the scalar-memory latency is paid once per 32 (column, weight) pairs; the stream carries
-    // one spare batch at its end, so the fetch of a short last batch stays in bounds
-    for (int remaining = sl.len; remaining > 0; remaining -= kBatchSlots, sp += 8 * kBatchSlots) {
-      // four 64-byte wave-uniform loads issued back to back; the empty asm statements pin all
-      // of them in scalar registers here, so the compiler cannot sink each load next to its
-      // (conditional) use and pay the scalar-memory latency four times
-      typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
-      static_assert(kBatchSlots == 8, "batch = four 16-dword fetches");
-      u32x16 q0 = *reinterpret_cast<const u32x16*>(sp);
-      u32x16 q1 = *reinterpret_cast<const u32x16*>(sp + 16);
-      u32x16 q2 = *reinterpret_cast<const u32x16*>(sp + 32);
-      u32x16 q3 = *reinterpret_cast<const u32x16*>(sp + 48);
-      asm volatile("" : "+s"(q0), "+s"(q1), "+s"(q2), "+s"(q3));
-      uint32_t cw[8 * kBatchSlots];
+        for (int e = 0; e < TPL; ++e) acc[r][e] = 0.0f;
+      // one batch = kBatchSlots slots = 64 dwords fetched with four back-to-back scalar loads, so
+      // the scalar-memory latency is paid once per 32 (offset, weight) pairs; the stream carries
+      // one spare batch at its end, so the fetch of a short last batch stays in bounds
+      for (int remaining = sl.len; remaining > 0; remaining -= kBatchSlots, sp += 8 * kBatchSlots) {
+        // the empty asm statement pins all four loads in scalar registers here, so the compiler
+        // cannot sink each load next to its (conditional) use and pay the latency four times
+        typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+        static_assert(kBatchSlots == 8 && kSlotUnroll == 2, "batch = four 16-dword fetches of two slots");
+        u32x16 q[4];
+        q[0] = *reinterpret_cast<const u32x16*>(sp);
+        q[1] = *reinterpret_cast<const u32x16*>(sp + 16);
+        q[2] = *reinterpret_cast<const u32x16*>(sp + 32);
+        q[3] = *reinterpret_cast<const u32x16*>(sp + 48);
+        asm volatile("" : "+s"(q[0]), "+s"(q[1]), "+s"(q[2]), "+s"(q[3]));
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        cw[e] = q0[e];
-        cw[16 + e] = q1[e];
-        cw[32 + e] = q2[e];
-        cw[48 + e] = q3[e];
-      }
+        for (int u = 0; u < 4; ++u) {  // two slots = eight non-zeros at a time
+          if (u * kSlotUnroll < remaining) {  // wave-uniform
+            // dword layout of two slots: off[4] w[4] off[4] w[4]
+            const uint32_t off[8] = {q[u][0], q[u][1], q[u][2], q[u][3], q[u][8], q[u][9], q[u][10], q[u][11]};
+            const float w[8] = {__uint_as_float(q[u][4]),  __uint_as_float(q[u][5]),  __uint_as_float(q[u][6]),
+                                __uint_as_float(q[u][7]),  __uint_as_float(q[u][12]), __uint_as_float(q[u][13]),
+                                __uint_as_float(q[u][14]), __uint_as_float(q[u][15])};
+            [[maybe_unused]] float x[8];
+            if constexpr (TPL == 1) {
+              panel_read8(off, x);
 #pragma unroll
-      for (int u = 0; u < kBatchSlots; u += kSlotUnroll) {
-        if (u < remaining) {  // wave-uniform
+              for (int e = 0; e < 8; ++e) acc[e & 3][0] = fmaf(w[e], x[e], acc[e & 3][0]);
+            } else {
 #pragma unroll
-          for (int uu = u; uu < u + kSlotUnroll; ++uu)
-#pragma unroll
-            for (int r = 0; r < kSliceRows; ++r) {
-              const float w = __uint_as_float(cw[uu * 8 + 4 + r]);
-              const float* vrow = lane_panel + cw[uu * 8 + r] * TB;
-#pragma unroll
-              for (int e = 0; e < TPL; ++e) acc[r][e] = fmaf(w, vrow[e], acc[r][e]);
+              for (int e = 0; e < 8; ++e) {
+                const float2 v2 = *reinterpret_cast<const float2*>(
+                    reinterpret_cast<const char*>(lane_panel) + off[e]);
+                acc[e & 3][0] = fmaf(w[e], v2.x, acc[e & 3][0]);
+                acc[e & 3][1] = fmaf(w[e], v2.y, acc[e & 3][1]);
+              }
             }
+          }
         }
       }
-    }
 #pragma unroll
-    for (int r = 0; r < kSliceRows; ++r) {
-      const int k = sorted_rows[sl.row0 + r];
-      if (k >= 0) {
-        float* dst = Mbuf + ((size_t)it.p * K + k) * Tp + tau0 + lane * TPL;
-#pragma unroll
-        for (int e = 0; e < TPL; ++e) dst[e] = acc[r][e];
+      for (int r = 0; r < kSliceRows; ++r) {
+        const int k = sl.k[r];
+        if (k >= 0 && lane_active) {
+          float* dst = Mbuf + ((size_t)it.p * K + k) * Tp + tau0 + lane * TPL;
+          if constexpr (TPL == 1)
+            dst[0] = acc[r][0];
+          else
+            *reinterpret_cast<float2*>(dst) = make_float2(acc[r][0], acc[r][1]);
+        }
       }
+      if (s_next >= it.slice_end) break;
+      s = s_next;
+      sl = sl_next;
     }
   }
 }
