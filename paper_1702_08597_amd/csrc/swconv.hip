@@ -192,7 +192,7 @@ void build_schedule(swconv_plan* pl, const std::vector<int64_t>& pos_cost) {
   const int64_t panel_cost = (int64_t)env_int("SWCONV_SPMM_PANEL_COST", 40) * pl->waves;
   const int64_t total_cost = std::accumulate(pos_cost.begin(), pos_cost.end(), (int64_t)0) * ntb;
   const int wgs_max = std::max(1, pl->n_wgs);
-  const int items_per_wg = std::max(1, env_int("SWCONV_SPMM_ITEMS_PER_WG", 2));
+  const int items_per_wg = std::max(1, env_int("SWCONV_SPMM_ITEMS_PER_WG", 3));
   const int64_t cost_per_item = std::max<int64_t>(1, total_cost / ((int64_t)wgs_max * items_per_wg));
 
   struct Item { WorkItem w; int64_t cost; int64_t slots; int panel; };
