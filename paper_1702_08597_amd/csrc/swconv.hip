@@ -19,7 +19,6 @@ using namespace swconv;
 namespace {
 
 constexpr int kMaxLdsBytes = 160 * 1024;
-constexpr int kSliceOverhead = 6;   // cost of starting/finishing a slice, in slots
 
 int env_int(const char* name, int dflt) {
   const char* s = std::getenv(name);
@@ -65,12 +64,12 @@ struct swconv_plan {
   // host-side packed sparse weights
   bool have_sparse = false;
   int64_t nnz = 0, padded_nnz = 0, max_item = 0;
-  std::vector<uint32_t> stream;      // 8 dwords per slot: c0..c3, w0..w3
-  std::vector<Slice> slices;         // P * Kp/4
+  std::vector<uint32_t> stream;      // 8-dword groups of (row offset, weight) slots
+  std::vector<Slice> slices;         // P * Kp / kSliceRows
   std::vector<int32_t> sorted_rows;  // P * Kp: original row k of each sorted row, -1 = padding
   std::vector<int32_t> sorted_len;   // P * Kp: stored entries of each sorted row
-  std::vector<WorkItem> items;       // grouped by workgroup
-  std::vector<int32_t> wg_begin;     // n_wgs_used + 1 offsets into items
+  std::vector<WorkItem> items;       // in range order
+  std::vector<int32_t> wg_begin;     // n_wgs_used + 1 offsets into items, one range per workgroup
   int n_wgs = 512;                   // persistent workgroups the device can hold at once
   int n_wgs_used = 0;                // workgroups the current schedule uses
 
@@ -142,7 +141,8 @@ int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
     attr_set = true;
   }
   hipLaunchKernelGGL(kern, dim3(pl->n_wgs_used), dim3(NW * 64), lds, st, pl->dV, pl->dM, pl->d_stream, pl->d_slices,
-                     (int)pl->slices.size(), pl->d_items, pl->d_wg_begin, pl->g.C, pl->g.K, pl->g.Tp, pl->tb);
+                     (int)pl->slices.size(), pl->d_items, pl->d_wg_begin, pl->n_wgs_used, pl->g.C, pl->g.K, pl->g.Tp,
+                     pl->tb, pl->g.m_bytes);
   HIP_TRY(hipGetLastError());
   return SWCONV_OK;
 }
@@ -180,90 +180,84 @@ int validate_csr(const swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   return SWCONV_OK;
 }
 
-// Static schedule of the sparse product.  Each position is cut into strided slice subsets
-// ("chunks", as many as its cost warrants, so item costs are alike whatever the per-position
-// densities are); one work item = (position, tile block, chunk).  Panels (position, tile block)
-// are dealt to the 8 XCDs, heaviest first to the least loaded XCD, so that all items of a panel
-// share one L2; inside an XCD the items go, heaviest first, to the least loaded of that XCD's
-// persistent workgroups (workgroup b runs on XCD b % 8).  Every workgroup then walks its own
-// list, sorted by panel so that a panel already in LDS is reused.
-void build_schedule(swconv_plan* pl, const std::vector<int64_t>& pos_cost) {
-  const int P = pl->P, slices_per_pos = pl->Kp / kSliceRows, ntb = pl->n_tau_blocks;
-  const int64_t panel_cost = (int64_t)env_int("SWCONV_SPMM_PANEL_COST", 40) * pl->waves;
-  const int64_t total_cost = std::accumulate(pos_cost.begin(), pos_cost.end(), (int64_t)0) * ntb;
+// Slot e of a slice that starts at 8-dword group `group0`: 2 * kSliceRows dwords, offsets first.
+template <typename U32>
+U32* stream_slot(U32* stream, uint32_t group0, int32_t e) {
+  return stream + (size_t)group0 * 8 + (size_t)e * 2 * kSliceRows;
+}
+
+// Static schedule of the sparse product.  The units (position, tile block, slice), in that order,
+// form one sequence; it is cut into one contiguous range per persistent workgroup such that every
+// range costs about the same: a slice costs its stream length plus a fixed overhead, shared out
+// over the waves, and entering a new panel costs one panel load.  The smallest feasible cost per
+// range is found by bisection.  A range touches at most a few panels, consecutive ranges share
+// panels and weights (and, through xcd_contiguous_id, an XCD's L2), and the split adapts by
+// itself to positions of very different density.
+void build_schedule(swconv_plan* pl) {
+  const int P = pl->P, spp = pl->Kp / kSliceRows, ntb = pl->n_tau_blocks, nw = pl->waves;
+  // costs in units of one stream group processed by one wave
+  const int64_t slice_ovh = env_int("SWCONV_SPMM_SLICE_COST", 3);
+  const int64_t panel_cost = (int64_t)env_int("SWCONV_SPMM_PANEL_COST", 30) * nw;
   const int wgs_max = std::max(1, pl->n_wgs);
-  const int items_per_wg = std::max(1, env_int("SWCONV_SPMM_ITEMS_PER_WG", 3));
-  const int64_t cost_per_item = std::max<int64_t>(1, total_cost / ((int64_t)wgs_max * items_per_wg));
 
-  struct Item { WorkItem w; int64_t cost; int64_t slots; int panel; };
-  std::vector<Item> all;
-  std::vector<int64_t> panel_total((size_t)P * ntb, 0);
-  for (int p = 0; p < P; ++p) {
-    int chunks = (int)((pos_cost[p] + cost_per_item - 1) / cost_per_item);
-    chunks = std::max(1, std::min(chunks, std::max(1, slices_per_pos / pl->waves)));
-    const int s0 = p * slices_per_pos, s1 = s0 + slices_per_pos;
-    for (int ch = 0; ch < chunks; ++ch) {
-      int64_t slots = 0, cost = panel_cost;
-      for (int s = s0 + ch; s < s1; s += chunks) {
-        slots += pl->slices[s].len;
-        cost += pl->slices[s].len + kSliceOverhead;
-      }
+  auto cut = [&](int64_t budget, std::vector<WorkItem>* items, std::vector<int32_t>* begin) -> int {
+    int wgs = 0;
+    int64_t acc = 0;
+    bool open_wg = false;
+    if (items) { items->clear(); begin->assign(1, 0); }
+    auto close_wg = [&]() {
+      if (!open_wg) return;
+      ++wgs;
+      if (begin) begin->push_back((int32_t)items->size());
+      open_wg = false;
+      acc = 0;
+    };
+    for (int p = 0; p < P; ++p)
       for (int tb = 0; tb < ntb; ++tb) {
-        all.push_back(Item{WorkItem{p, tb, s0 + ch, s1, chunks, {0, 0, 0}}, cost, slots, p * ntb + tb});
-        panel_total[(size_t)p * ntb + tb] += cost;
+        int s = p * spp;
+        const int s_end = s + spp;
+        while (s < s_end) {
+          // a new item in the current workgroup: pay the panel, then take slices while they fit
+          if (open_wg && acc + panel_cost + pl->slices[s].len + slice_ovh > budget) close_wg();
+          open_wg = true;
+          acc += panel_cost;
+          const int s0 = s;
+          while (s < s_end) {
+            const int64_t c = pl->slices[s].len + slice_ovh;
+            if (s > s0 && acc + c > budget) break;
+            acc += c;
+            ++s;
+          }
+          if (items) items->push_back(WorkItem{p, tb, s0, s});
+          if (s < s_end) close_wg();
+        }
       }
-    }
-  }
-  const int n_wgs = (int)std::min<size_t>(wgs_max, all.size());
-  pl->n_wgs_used = n_wgs;
+    close_wg();
+    return wgs;
+  };
 
-  // panels -> XCDs (only XCDs that own at least one workgroup), normalised by workgroup count
-  int xcd_wgs[kXcds];
-  for (int x = 0; x < kXcds; ++x) xcd_wgs[x] = n_wgs / kXcds + (x < n_wgs % kXcds ? 1 : 0);
-  std::vector<int> porder(panel_total.size());
-  std::iota(porder.begin(), porder.end(), 0);
-  std::stable_sort(porder.begin(), porder.end(), [&](int a, int b) { return panel_total[a] > panel_total[b]; });
-  std::vector<int> panel_xcd(panel_total.size(), 0);
-  int64_t xcd_load[kXcds] = {0};
-  for (int pi : porder) {
-    int best = -1;
-    for (int x = 0; x < kXcds; ++x) {
-      if (xcd_wgs[x] == 0) continue;
-      // compare load per workgroup: load[x] / wgs[x] < load[best] / wgs[best]
-      if (best < 0 || xcd_load[x] * xcd_wgs[best] < xcd_load[best] * xcd_wgs[x]) best = x;
-    }
-    panel_xcd[pi] = best;
-    xcd_load[best] += panel_total[pi];
+  int64_t total = 0, biggest = 0;
+  for (const Slice& sl : pl->slices) {
+    total += sl.len + slice_ovh;
+    biggest = std::max<int64_t>(biggest, sl.len + slice_ovh);
   }
-
-  // items -> workgroups of the panel's XCD
-  std::vector<int> iorder(all.size());
-  std::iota(iorder.begin(), iorder.end(), 0);
-  std::stable_sort(iorder.begin(), iorder.end(), [&](int a, int b) { return all[a].cost > all[b].cost; });
-  std::vector<int64_t> wg_load(n_wgs, 0), wg_slots(n_wgs, 0);
-  std::vector<std::vector<int>> wg_items(n_wgs);
-  for (int ii : iorder) {
-    const int x = panel_xcd[all[ii].panel];
-    int best = -1;
-    for (int b = x; b < n_wgs; b += kXcds)
-      if (best < 0 || wg_load[b] < wg_load[best]) best = b;
-    wg_items[best].push_back(ii);
-    wg_load[best] += all[ii].cost;
-    wg_slots[best] += all[ii].slots;
+  total *= ntb;
+  int64_t lo = panel_cost + biggest, hi = std::max(lo, total + (int64_t)P * ntb * panel_cost);
+  while (lo < hi) {  // smallest budget that needs no more than wgs_max workgroups
+    const int64_t mid = lo + (hi - lo) / 2;
+    if (cut(mid, nullptr, nullptr) <= wgs_max) hi = mid; else lo = mid + 1;
   }
-  pl->items.clear();
-  pl->wg_begin.assign((size_t)n_wgs + 1, 0);
+  pl->n_wgs_used = cut(lo, &pl->items, &pl->wg_begin);
   pl->max_item = 0;
-  for (int b = 0; b < n_wgs; ++b) {
-    std::stable_sort(wg_items[b].begin(), wg_items[b].end(),
-                     [&](int a, int c) { return all[a].panel < all[c].panel; });
-    for (int ii : wg_items[b]) pl->items.push_back(all[ii].w);
-    pl->wg_begin[b + 1] = (int32_t)pl->items.size();
-    pl->max_item = std::max(pl->max_item, wg_slots[b] * kSliceRows);
+  for (int b = 0; b < pl->n_wgs_used; ++b) {
+    int64_t groups = 0;
+    for (int i = pl->wg_begin[b]; i < pl->wg_begin[b + 1]; ++i)
+      for (int sidx = pl->items[i].slice_begin; sidx < pl->items[i].slice_end; ++sidx) groups += pl->slices[sidx].len;
+    pl->max_item = std::max(pl->max_item, groups * 4);
   }
 }
 
-// Re-pack per-position CSR into the sliced layout and build the work list.
+// Re-pack per-position CSR into the sliced layout and build the schedule.
 void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, const float* vals) {
   const int P = pl->P, K = pl->g.K, Kp = pl->Kp;
   const int slices_per_pos = Kp / kSliceRows;
@@ -273,8 +267,7 @@ void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx,
   pl->slices.assign((size_t)P * slices_per_pos, Slice{});
 
   std::vector<int32_t> order(K);
-  std::vector<int64_t> pos_cost(P, 0);
-  uint64_t slot_cursor = 0;
+  uint64_t group_cursor = 0;
   for (int p = 0; p < P; ++p) {
     const int32_t* rp = rowptr + (int64_t)p * K;
     std::iota(order.begin(), order.end(), 0);
@@ -288,19 +281,18 @@ void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx,
       Slice& sl = pl->slices[(size_t)p * slices_per_pos + s];
       sl.p = p;
       sl.row0 = p * Kp + s * kSliceRows;
-      // rows are sorted: the first is the longest; round up to whole scalar fetches
-      sl.len = (pl->sorted_len[sl.row0] + kSlotUnroll - 1) / kSlotUnroll * kSlotUnroll;
-      sl.slot0 = (uint32_t)slot_cursor;
-      for (int r = 0; r < kSliceRows; ++r) sl.k[r] = pl->sorted_rows[sl.row0 + r];
-      slot_cursor += sl.len;
-      pos_cost[p] += sl.len + kSliceOverhead;
+      // rows are sorted: the first is the longest; whole groups of kGroupSlots slots
+      sl.len = (pl->sorted_len[sl.row0] + kGroupSlots - 1) / kGroupSlots;
+      sl.group0 = (uint32_t)group_cursor;
+      for (int r = 0; r < 4; ++r) sl.k[r] = r < kSliceRows ? pl->sorted_rows[sl.row0 + r] : -1;
+      group_cursor += sl.len;
     }
   }
-  pl->padded_nnz = (int64_t)slot_cursor * kSliceRows;
+  pl->padded_nnz = (int64_t)group_cursor * 4;
   // a slot entry is (byte offset of the panel row of column c, weight); padding = row 0,
   // weight +0.0f; one spare batch at the end keeps the kernel's whole-batch fetches in bounds
   const uint32_t row_bytes = (uint32_t)pl->tb * sizeof(float);
-  pl->stream.assign(((size_t)slot_cursor + kBatchSlots) * 8, 0u);
+  pl->stream.assign(((size_t)group_cursor + kBatchGroups) * 8, 0u);
   for (size_t s = 0; s < pl->slices.size(); ++s) {
     const Slice& sl = pl->slices[s];
     const int32_t* rp = rowptr + (int64_t)sl.p * K;
@@ -309,14 +301,13 @@ void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx,
       if (k < 0) continue;
       const int32_t q0 = rp[k], len = rp[k + 1] - rp[k];
       for (int32_t e = 0; e < len; ++e) {
-        uint32_t* slot = pl->stream.data() + ((size_t)sl.slot0 + e) * 8;
+        uint32_t* slot = stream_slot(pl->stream.data(), sl.group0, e);
         slot[r] = (uint32_t)colidx[q0 + e] * row_bytes;
-        std::memcpy(&slot[4 + r], &vals[q0 + e], sizeof(float));
+        std::memcpy(&slot[kSliceRows + r], &vals[q0 + e], sizeof(float));
       }
     }
   }
-
-  build_schedule(pl, pos_cost);
+  build_schedule(pl);
   pl->have_sparse = true;
 }
 
@@ -403,6 +394,13 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   // row pitch of V and M: whole tile blocks of the sparse product, and a multiple of 128 for the
   // transform kernels (64-tile blocks) and the dense comparison GEMM (128-tile blocks)
   g.Tp = (int)(((T + tb - 1) / tb * tb + 127) / 128 * 128);
+  // V and M are addressed with 32-bit byte offsets (buffer descriptors)
+  if ((int64_t)P * std::max(C, K) * g.Tp * (int64_t)sizeof(float) >= ((int64_t)1 << 32) - 256) {
+    delete pl;
+    return SWCONV_EUNSUPPORTED;
+  }
+  g.v_bytes = (uint32_t)((int64_t)P * C * g.Tp * (int64_t)sizeof(float));
+  g.m_bytes = (uint32_t)((int64_t)P * K * g.Tp * (int64_t)sizeof(float));
   // LDS staging bounds of the transform kernels for any run of 64 consecutive tiles
   const int rows_t = (int)std::min<int64_t>(th, (64 + tw - 2) / tw + 1);
   g.slots = (int)std::min<int64_t>(N, (64 + g.tpi - 2) / g.tpi + 1);
@@ -535,9 +533,9 @@ int swconv_debug_export_weights(swconv_plan* pl, int32_t* rowptr, int32_t* colid
       if (k < 0) continue;
       const int32_t q0 = rowptr[(int64_t)sl.p * K + k];
       for (int32_t e = 0; e < pl->sorted_len[sl.row0 + r]; ++e) {
-        const uint32_t* slot = pl->stream.data() + ((size_t)sl.slot0 + e) * 8;
+        const uint32_t* slot = stream_slot(pl->stream.data(), sl.group0, e);
         colidx[q0 + e] = (int32_t)(slot[r] / ((uint32_t)pl->tb * sizeof(float)));
-        std::memcpy(&vals[q0 + e], &slot[4 + r], sizeof(float));
+        std::memcpy(&vals[q0 + e], &slot[kSliceRows + r], sizeof(float));
       }
     }
   return SWCONV_OK;

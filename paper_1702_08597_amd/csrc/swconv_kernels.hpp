@@ -25,7 +25,27 @@ struct Geometry {
   // LDS staging of the transforms: a block of 64 consecutive tiles touches at most `slots` images,
   // and in each of them a run of at most `in_span` input / `out_span` output floats (whole rows)
   int slots, in_span, out_span;
+  uint32_t v_bytes, m_bytes;  // sizes of the V and M workspaces (both below 4 GiB)
 };
+
+// V and M are addressed through buffer descriptors: address = base + scalar byte offset (the
+// row, wave-uniform) + vector byte offset (the lane), so a row access costs no vector address
+// arithmetic; accesses past `bytes` are dropped by the hardware.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float buffer_load_f32(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+}
+__device__ __forceinline__ void buffer_store_f32(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, float x) {
+  __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, x), r, (int)voff, (int)soff, 0);
+}
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void buffer_store_f32x2(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff, float x,
+                                                   float y) {
+  u32x2_t d = {__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, y)};
+  __builtin_amdgcn_raw_buffer_store_b64(d, r, (int)voff, (int)soff, 0);
+}
 
 // The part of image n that a block of 64 consecutive tiles [tau0, last] covers.
 struct ImagePart {
@@ -43,28 +63,26 @@ __device__ __forceinline__ ImagePart image_part(const Geometry& g, int n, int ta
   return ip;
 }
 
-// One slice = four rows of one position's sparse matrix, rows sorted by length.  32 bytes, so a
-// wave fetches a whole descriptor with one scalar load.
+// One slice = kSliceRows rows of one position's sparse matrix, rows sorted by length.  32 bytes,
+// so a wave fetches a whole descriptor with one scalar load.
 struct Slice {
-  uint32_t slot0;  // first slot of the slice in the packed stream (8 dwords per slot)
-  int32_t len;     // slots in the slice = length of its longest row, rounded up to kSlotUnroll
-  int32_t row0;    // index of its first row in the host's sorted-row table (P * Kp entries)
-  int32_t p;       // position
-  int32_t k[4];    // output channel of each of the four rows, -1 = padding row
+  uint32_t group0;  // first 8-dword group of the slice in the packed stream
+  int32_t len;      // groups in the slice (4 (row offset, weight) pairs each)
+  int32_t row0;     // index of its first row in the host's sorted-row table (P * Kp entries)
+  int32_t p;        // position
+  int32_t k[4];     // output channel of each row (first kSliceRows entries), -1 = padding row
 };
 
-// One unit of the sparse product: a tile block of one position and a strided subset of that
-// position's slices.  32 bytes.
+// One unit of the schedule: a contiguous run of slices of one position, for one tile block.
 struct WorkItem {
   int32_t p;
   int32_t tau_block;
-  int32_t slice_begin;  // first slice taken
-  int32_t slice_end;    // one past the position's last slice
-  int32_t stride;       // distance between slices taken
-  int32_t pad[3];
+  int32_t slice_begin;  // first slice
+  int32_t slice_end;    // one past the last slice
 };
 
-constexpr int kSliceRows = 4;
+constexpr int kSliceRows = 2;   // rows per slice
+constexpr int kGroupSlots = 4 / kSliceRows;  // slots (one pair per row) in an 8-dword stream group
 constexpr int kXcds = 8;
 
 // Workgroup ids are dealt round-robin to the 8 XCDs; remap them so that each XCD gets one
@@ -85,29 +103,57 @@ __device__ __forceinline__ void decode_tile(const Geometry& g, int tau, int& n, 
 // ---------------------------------------------------------------------------------------------
 // Step 1: gather phi + V = B^T d B.  A wave owns one channel and 64 consecutive tiles: it copies
 // the input rows those tiles touch into its private LDS area with lane-contiguous (coalesced)
-// loads - each pixel is read from memory once although up to (t/m)^2 tiles use it - then every
-// lane gathers its t x t tile from LDS (zero outside the image), transforms it in registers and
-// stores one value per position: 64 lanes -> 256 contiguous bytes of V[p][c][.].
+// loads - each pixel is read from memory once although up to (t/m)^2 tiles use it; the loads of
+// up to four images are all in flight before the first LDS write - then every lane gathers its
+// t x t tile from LDS (clamped addresses, all reads issued back to back, then selects zero what
+// lies outside the image), transforms it in registers and stores one value per position:
+// 64 lanes -> 256 contiguous bytes of V[p][c][.], addressed as wave-uniform base + lane.
 // Block = 4 waves = 4 channels of the same tile block.
 template <int M>
 __global__ __launch_bounds__(256) void input_transform_kernel(const float* __restrict__ in, float* __restrict__ V,
                                                               const Geometry g) {
   constexpr int t = Wino<M>::t;
   extern __shared__ float stage[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = blockIdx.y * 4 + wave;
   const int tau0 = blockIdx.x * 64;
   const int last = min(tau0 + 63, g.T - 1);
   const int n_first = tau0 / g.tpi, n_last = last / g.tpi;
   float* my = stage + wave * g.slots * g.in_span;
   if (c < g.C) {
-    for (int n = n_first; n <= n_last; ++n) {
-      const ImagePart ip = image_part(g, n, tau0, last);
-      const int y_lo = max(0, ip.ty_lo * M - g.pad), y_hi = min(g.H, ip.ty_hi * M - g.pad + t);
-      const int span = (y_hi - y_lo) * g.W;
-      const float* src = in + (((size_t)n * g.C + c) * g.H + y_lo) * g.W;
-      float* dst = my + (n - n_first) * g.in_span;
-      for (int e = lane; e < span; e += 64) dst[e] = src[e];
+    constexpr int IG = 4, EL = 4;  // images x loads per lane in flight
+    for (int n0 = n_first; n0 <= n_last; n0 += IG) {
+      const float* src[IG];
+      float* dst[IG];
+      int span[IG], max_span = 0;
+#pragma unroll
+      for (int i = 0; i < IG; ++i) {
+        const int n = min(n0 + i, n_last);
+        const ImagePart ip = image_part(g, n, tau0, last);
+        const int y_lo = max(0, ip.ty_lo * M - g.pad), y_hi = min(g.H, ip.ty_hi * M - g.pad + t);
+        span[i] = n0 + i <= n_last ? (y_hi - y_lo) * g.W : 0;
+        src[i] = in + (((size_t)n * g.C + c) * g.H + y_lo) * g.W;
+        dst[i] = my + (n - n_first) * g.in_span;
+        max_span = max(max_span, span[i]);
+      }
+      for (int e0 = 0; e0 < max_span; e0 += 64 * EL) {
+        float buf[IG][EL];
+#pragma unroll
+        for (int i = 0; i < IG; ++i)
+#pragma unroll
+          for (int u = 0; u < EL; ++u) {
+            const int e = e0 + u * 64 + lane;
+            buf[i][u] = e < span[i] ? src[i][e] : 0.0f;
+          }
+#pragma unroll
+        for (int i = 0; i < IG; ++i)
+#pragma unroll
+          for (int u = 0; u < EL; ++u) {
+            const int e = e0 + u * 64 + lane;
+            if (e < span[i]) dst[i][e] = buf[i][u];
+          }
+      }
     }
   }
   __syncthreads();
@@ -115,13 +161,11 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
   const int tau = tau0 + lane;
   float d[t][t];
   {
-    // every lane reads t*t LDS words at clamped (always valid) addresses and zeroes what lies
-    // outside the image or belongs to a padding tile: selects, no divergent branches
     const bool live = tau < g.T;
     int n, ty, tx;
     decode_tile(g, live ? tau : tau0, n, ty, tx);
     const ImagePart ip = image_part(g, n, tau0, last);
-    const int y_lo = max(0, ip.ty_lo * M - g.pad);
+    const int y_lo = max(0, ip.ty_lo * M - g.pad), y_hi = min(g.H, ip.ty_hi * M - g.pad + t);
     const float* img = my + (n - n_first) * g.in_span - y_lo * g.W;
     const int y0 = ty * M - g.pad, x0 = tx * M - g.pad;
     int xo[t];
@@ -135,62 +179,72 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
 #pragma unroll
     for (int i = 0; i < t; ++i) {
       const int y = y0 + i;
-      const bool yok = y >= 0 && y < g.H;
-      const float* row = img + min(max(y, y_lo), g.H - 1) * g.W;
+      const float* row = img + min(max(y, y_lo), y_hi - 1) * g.W;  // a staged row in any case
 #pragma unroll
-      for (int j = 0; j < t; ++j) {
-        const float val = row[xo[j]];
-        d[i][j] = (yok && xok[j]) ? val : 0.0f;
-      }
+      for (int j = 0; j < t; ++j) d[i][j] = row[xo[j]];
+    }
+    // all t*t reads are issued above; pinning the values here keeps the compiler from turning
+    // the selects below into one guarded (and serialised) read each
+#pragma unroll
+    for (int i = 0; i < t; ++i) {
+      if constexpr (t == 6)
+        asm volatile("" : "+v"(d[i][0]), "+v"(d[i][1]), "+v"(d[i][2]), "+v"(d[i][3]), "+v"(d[i][4]), "+v"(d[i][5]));
+      else
+        asm volatile("" : "+v"(d[i][0]), "+v"(d[i][1]), "+v"(d[i][2]), "+v"(d[i][3]));
+    }
+#pragma unroll
+    for (int i = 0; i < t; ++i) {
+      const int y = y0 + i;
+      const bool yok = y >= 0 && y < g.H;
+#pragma unroll
+      for (int j = 0; j < t; ++j) d[i][j] = (yok && xok[j]) ? d[i][j] : 0.0f;
     }
   }
   float v[t][t];
   input_transform<M>(d, v);
-  float* dst = V + (size_t)c * g.Tp + tau;
-  const size_t pstride = (size_t)g.C * g.Tp;
+  const __amdgpu_buffer_rsrc_t vr = make_rsrc(V, g.v_bytes);
+  const uint32_t row0 = ((uint32_t)c * g.Tp + tau0) * 4u;        // wave-uniform byte offset, position 0
+  const uint32_t pstride = (uint32_t)g.C * (uint32_t)g.Tp * 4u;  // bytes between positions
 #pragma unroll
   for (int i = 0; i < t; ++i)
 #pragma unroll
-    for (int j = 0; j < t; ++j) dst[(i * t + j) * pstride] = v[i][j];
+    for (int j = 0; j < t; ++j) buffer_store_f32(vr, lane * 4u, row0 + (i * t + j) * pstride, v[i][j]);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Step 2: M[p] = W_F[p] * V[p] on the plain fp32 ALUs.
 //
-// Persistent workgroups: workgroup b walks the work items [wg_begin[b], wg_begin[b+1]) that the
-// host's static schedule gave it (equal cost per workgroup, items of one panel kept together and
-// on one XCD).  For an item it stages the C x TB panel V[p][:, tau_block] in LDS (unless the
-// previous item used the same panel), then each wave walks its share of the item's slices.
+// Persistent workgroups: the host cuts the sequence of all (position, tile block, slice) units
+// into one contiguous, equal-cost range per workgroup; range r is run by the workgroup whose id
+// maps to r under xcd_contiguous_id, so neighbouring ranges - which share panels and weights -
+// share an XCD's L2.  A range is a short list of work items (runs of slices of one panel).  For an
+// item the workgroup stages the C x TB panel V[p][:, tau_block] in LDS (unless it is already
+// there), then the waves take the item's slices round-robin.
 //
-// A slice's stream is a sequence of slots, each holding one (panel row byte offset, weight) pair
-// for each of the slice's four rows.  Per batch of eight slots the wave fetches 64 dwords with
-// four back-to-back wave-uniform (scalar) loads; weights stay in scalar registers, there is one
-// vector accumulator per row and tile.
+// A slice's stream is a sequence of 8-dword groups; a group holds kGroupSlots slots, a slot one
+// (panel row byte offset, weight) pair for each of the slice's kSliceRows rows.  Per batch of
+// eight groups the wave fetches 64 dwords with four back-to-back wave-uniform (scalar) loads;
+// weights stay in scalar registers, there is one vector accumulator per row and tile.
 //
-// LDS is the binding unit: a CU retires about one LDS instruction per 4-5 clocks whatever its
-// width up to 8 bytes per lane, so the kernel reads two tiles per lane with one 8-byte access
-// (TPL = 2, tile block TB <= 128 chosen so that the panel fits LDS) wherever that feeds more
-// FMAs per LDS instruction than one tile per lane does.  With TPL = 1 (TB = 64) the panel
-// operand is read with ds_read_addtid_b32, whose address is M0 + 4 * lane: the row offset goes
-// from its scalar register straight into M0 and no vector address arithmetic is spent.
-constexpr int kSlotUnroll = 2;   // slice lengths are multiples of this many slots
-constexpr int kBatchSlots = 8;   // slots fetched per scalar-memory round trip
+// LDS is the binding unit: a CU retires one LDS instruction per 4 clocks whatever its width up to
+// 8 bytes per lane (5.3 clocks for 16 bytes), so the kernel reads two tiles per lane with one
+// 8-byte access (TPL = 2, tile block TB <= 128 chosen so that the panel fits LDS) wherever that
+// feeds more FMAs per LDS instruction than one tile per lane does.  With TPL = 1 (TB = 64) the
+// panel operand is read with ds_read_addtid_b32, whose address is M0 + 4 * lane: the row offset
+// goes from its scalar register straight into M0 and no vector address arithmetic is spent.
+constexpr int kBatchGroups = 8;  // 8-dword groups fetched per scalar-memory round trip
 
-// Eight panel reads for eight wave-uniform row offsets.  One wait state is required between the
+// Four panel reads for four wave-uniform row offsets.  One wait state is required between the
 // write of M0 and an LDS add-TID instruction (s_nop 0).  The loads are complete on return.
-__device__ __forceinline__ void panel_read8(const uint32_t (&off)[8], float (&x)[8]) {
+__device__ __forceinline__ void panel_read4(const uint32_t (&off)[4], float (&x)[4]) {
   asm volatile(
-      "s_mov_b32 m0, %8\n s_nop 0\n ds_read_addtid_b32 %0\n"
-      "s_mov_b32 m0, %9\n s_nop 0\n ds_read_addtid_b32 %1\n"
-      "s_mov_b32 m0, %10\n s_nop 0\n ds_read_addtid_b32 %2\n"
-      "s_mov_b32 m0, %11\n s_nop 0\n ds_read_addtid_b32 %3\n"
-      "s_mov_b32 m0, %12\n s_nop 0\n ds_read_addtid_b32 %4\n"
-      "s_mov_b32 m0, %13\n s_nop 0\n ds_read_addtid_b32 %5\n"
-      "s_mov_b32 m0, %14\n s_nop 0\n ds_read_addtid_b32 %6\n"
-      "s_mov_b32 m0, %15\n s_nop 0\n ds_read_addtid_b32 %7\n"
+      "s_mov_b32 m0, %4\n s_nop 0\n ds_read_addtid_b32 %0\n"
+      "s_mov_b32 m0, %5\n s_nop 0\n ds_read_addtid_b32 %1\n"
+      "s_mov_b32 m0, %6\n s_nop 0\n ds_read_addtid_b32 %2\n"
+      "s_mov_b32 m0, %7\n s_nop 0\n ds_read_addtid_b32 %3\n"
       "s_waitcnt lgkmcnt(0)"
-      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3]), "=&v"(x[4]), "=&v"(x[5]), "=&v"(x[6]), "=&v"(x[7])
-      : "s"(off[0]), "s"(off[1]), "s"(off[2]), "s"(off[3]), "s"(off[4]), "s"(off[5]), "s"(off[6]), "s"(off[7])
+      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3])
+      : "s"(off[0]), "s"(off[1]), "s"(off[2]), "s"(off[3])
       : "memory");
 }
 
@@ -199,18 +253,21 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
                                                            const uint32_t* __restrict__ stream,
                                                            const Slice* __restrict__ slices, int n_slices,
                                                            const WorkItem* __restrict__ items,
-                                                           const int32_t* __restrict__ wg_begin, int C, int K,
-                                                           int Tp, int TB) {
+                                                           const int32_t* __restrict__ wg_begin, int n_wgs, int C,
+                                                           int K, int Tp, int TB, uint32_t m_bytes) {
   constexpr int NT = NWAVES * 64;
   extern __shared__ float panel[];  // [C][TB], at LDS offset 0 of the workgroup
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int item_begin = wg_begin[blockIdx.x], item_end = wg_begin[blockIdx.x + 1];
+  const int range = xcd_contiguous_id(blockIdx.x, n_wgs);
+  const int item_begin = wg_begin[range], item_end = wg_begin[range + 1];
   int cur_p = -1, cur_tb = -1;
   // TPL = 2: lane l owns the adjacent tiles 2l, 2l+1 of the block and reads them with one 8-byte
   // LDS access; when TB < 128 the lanes past TB/2 idle (they read lane 0's words, store nothing)
   const bool lane_active = TPL == 1 || 2 * lane < TB;
   const float* lane_panel = panel + (lane_active ? lane * TPL : 0);
+  const __amdgpu_buffer_rsrc_t mr = make_rsrc(Mbuf, m_bytes);
+  const uint32_t m_lane_off = lane_active ? lane * TPL * 4u : 0xfffffff0u;
 
   for (int item = item_begin; item < item_end; ++item) {
     const WorkItem it = items[item];
@@ -223,7 +280,7 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
       // before its first LDS write
       const float* src = V + ((size_t)it.p * C) * Tp + tau0;
       const int V4_PER_ROW = TB / 4;
-      constexpr int U = 4;
+      constexpr int U = 8;
       const int total = C * V4_PER_ROW;
       int base = threadIdx.x;
       for (; base + (U - 1) * NT < total; base += NT * U) {  // full batches, no bounds checks
@@ -245,29 +302,28 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
       __syncthreads();
     }
 
-    const int step = NWAVES * it.stride;
-    int s = it.slice_begin + wave * it.stride;
+    int s = it.slice_begin + wave;
     if (s >= it.slice_end) continue;
     Slice sl = slices[s];
     while (true) {
       // descriptor of this wave's next slice, fetched while the current one is computed (the
       // index is clamped, so the load is unconditional and in bounds)
-      const int s_next = s + step;
+      const int s_next = s + NWAVES;
       const Slice sl_next = slices[min(s_next, n_slices - 1)];
-      const uint32_t* sp = stream + (size_t)sl.slot0 * 8;
+      const uint32_t* sp = stream + (size_t)sl.group0 * 8;
       float acc[kSliceRows][TPL];
 #pragma unroll
       for (int r = 0; r < kSliceRows; ++r)
 #pragma unroll
         for (int e = 0; e < TPL; ++e) acc[r][e] = 0.0f;
-      // one batch = kBatchSlots slots = 64 dwords fetched with four back-to-back scalar loads, so
-      // the scalar-memory latency is paid once per 32 (offset, weight) pairs; the stream carries
-      // one spare batch at its end, so the fetch of a short last batch stays in bounds
-      for (int remaining = sl.len; remaining > 0; remaining -= kBatchSlots, sp += 8 * kBatchSlots) {
+      // one batch = kBatchGroups groups = 64 dwords fetched with four back-to-back scalar loads,
+      // so the scalar-memory latency is paid once per 32 (offset, weight) pairs; the stream
+      // carries one spare batch at its end, so the fetch of a short last batch stays in bounds
+      for (int remaining = sl.len; remaining > 0; remaining -= kBatchGroups, sp += 8 * kBatchGroups) {
         // the empty asm statement pins all four loads in scalar registers here, so the compiler
         // cannot sink each load next to its (conditional) use and pay the latency four times
         typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
-        static_assert(kBatchSlots == 8 && kSlotUnroll == 2, "batch = four 16-dword fetches of two slots");
+        static_assert(kBatchGroups == 8, "batch = four 16-dword fetches");
         u32x16 q[4];
         q[0] = *reinterpret_cast<const u32x16*>(sp);
         q[1] = *reinterpret_cast<const u32x16*>(sp + 16);
@@ -275,25 +331,30 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
         q[3] = *reinterpret_cast<const u32x16*>(sp + 48);
         asm volatile("" : "+s"(q[0]), "+s"(q[1]), "+s"(q[2]), "+s"(q[3]));
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {  // two slots = eight non-zeros at a time
-          if (u * kSlotUnroll < remaining) {  // wave-uniform
-            // dword layout of two slots: off[4] w[4] off[4] w[4]
-            const uint32_t off[8] = {q[u][0], q[u][1], q[u][2], q[u][3], q[u][8], q[u][9], q[u][10], q[u][11]};
-            const float w[8] = {__uint_as_float(q[u][4]),  __uint_as_float(q[u][5]),  __uint_as_float(q[u][6]),
-                                __uint_as_float(q[u][7]),  __uint_as_float(q[u][12]), __uint_as_float(q[u][13]),
-                                __uint_as_float(q[u][14]), __uint_as_float(q[u][15])};
-            [[maybe_unused]] float x[8];
-            if constexpr (TPL == 1) {
-              panel_read8(off, x);
+        for (int g = 0; g < kBatchGroups; ++g) {  // one group = four non-zeros
+          if (g < remaining) {                    // wave-uniform
+            // dword layout of a group: per slot, kSliceRows offsets then kSliceRows weights
+            uint32_t off[4];
+            float w[4];
 #pragma unroll
-              for (int e = 0; e < 8; ++e) acc[e & 3][0] = fmaf(w[e], x[e], acc[e & 3][0]);
+            for (int e = 0; e < 4; ++e) {
+              const int slot = e / kSliceRows, r = e % kSliceRows;
+              const int d = (g & 1) * 8 + slot * 2 * kSliceRows + r;
+              off[e] = q[g >> 1][d];
+              w[e] = __uint_as_float(q[g >> 1][d + kSliceRows]);
+            }
+            if constexpr (TPL == 1) {
+              float x[4];
+              panel_read4(off, x);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[e % kSliceRows][0] = fmaf(w[e], x[e], acc[e % kSliceRows][0]);
             } else {
 #pragma unroll
-              for (int e = 0; e < 8; ++e) {
+              for (int e = 0; e < 4; ++e) {
                 const float2 v2 = *reinterpret_cast<const float2*>(
                     reinterpret_cast<const char*>(lane_panel) + off[e]);
-                acc[e & 3][0] = fmaf(w[e], v2.x, acc[e & 3][0]);
-                acc[e & 3][1] = fmaf(w[e], v2.y, acc[e & 3][1]);
+                acc[e % kSliceRows][0] = fmaf(w[e], v2.x, acc[e % kSliceRows][0]);
+                acc[e % kSliceRows][1] = fmaf(w[e], v2.y, acc[e % kSliceRows][1]);
               }
             }
           }
@@ -302,12 +363,12 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
 #pragma unroll
       for (int r = 0; r < kSliceRows; ++r) {
         const int k = sl.k[r];
-        if (k >= 0 && lane_active) {
-          float* dst = Mbuf + ((size_t)it.p * K + k) * Tp + tau0 + lane * TPL;
+        if (k >= 0) {  // wave-uniform; idle lanes are parked beyond the buffer, their store is dropped
+          const uint32_t row = (((uint32_t)it.p * K + k) * Tp + tau0) * 4u;
           if constexpr (TPL == 1)
-            dst[0] = acc[r][0];
+            buffer_store_f32(mr, m_lane_off, row, acc[r][0]);
           else
-            *reinterpret_cast<float2*>(dst) = make_float2(acc[r][0], acc[r][1]);
+            buffer_store_f32x2(mr, m_lane_off, row, acc[r][0], acc[r][1]);
         }
       }
       if (s_next >= it.slice_end) break;
@@ -329,7 +390,8 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
                                                                float* __restrict__ out, const Geometry g) {
   constexpr int t = Wino<M>::t;
   extern __shared__ float stage[];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int k = blockIdx.y * 4 + wave;
   const int tau0 = blockIdx.x * 64;
   if (tau0 >= g.T) return;  // whole block is padding (uniform for the block)
@@ -338,13 +400,14 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
   const int tau = tau0 + lane;
   float* my = stage + wave * g.slots * g.out_span;
   if (k < g.K && tau < g.T) {
-    const float* msrc = Mbuf + (size_t)k * g.Tp + tau;
-    const size_t pstride = (size_t)g.K * g.Tp;
+    const __amdgpu_buffer_rsrc_t mr = make_rsrc(Mbuf, g.m_bytes);
+    const uint32_t row0 = ((uint32_t)k * g.Tp + tau0) * 4u;        // wave-uniform byte offset, position 0
+    const uint32_t pstride = (uint32_t)g.K * (uint32_t)g.Tp * 4u;  // bytes between positions
     float z[t][t];
 #pragma unroll
     for (int i = 0; i < t; ++i)
 #pragma unroll
-      for (int j = 0; j < t; ++j) z[i][j] = msrc[(i * t + j) * pstride];
+      for (int j = 0; j < t; ++j) z[i][j] = buffer_load_f32(mr, lane * 4u, row0 + (i * t + j) * pstride);
     float y[M][M];
     output_transform<M>(z, y);
     int n, ty, tx;
