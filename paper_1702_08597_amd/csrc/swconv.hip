@@ -73,6 +73,12 @@ struct swconv_plan {
   int n_wgs = 512;                   // persistent workgroups the device can hold at once
   int n_wgs_used = 0;                // workgroups the current schedule uses
 
+  // host-built index tables of the transform kernels
+  std::vector<TileInfo> tiles;        // Tp
+  std::vector<BlockImage> blocks;     // Tp/64 * slots
+  TileInfo* d_tiles = nullptr;
+  BlockImage* d_blocks = nullptr;
+
   // device
   bool on_device = false, sparse_on_device = false, dense_on_device = false, ran_forward = false;
   float *dV = nullptr, *dM = nullptr;
@@ -96,6 +102,9 @@ int ensure_workspace(swconv_plan* pl) {
   HIP_TRY(hipMalloc((void**)&pl->dM, mbytes));
   HIP_TRY(hipMemset(pl->dV, 0, vbytes));
   HIP_TRY(hipMemset(pl->dM, 0, mbytes));
+  int rc;
+  if ((rc = upload(&pl->d_tiles, pl->tiles))) return rc;
+  if ((rc = upload(&pl->d_blocks, pl->blocks))) return rc;
   pl->on_device = true;
   return SWCONV_OK;
 }
@@ -110,7 +119,7 @@ int launch_input_transform(const swconv_plan* pl, hipStream_t st, const float* i
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, in, pl->dV, pl->g);
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, in, pl->dV, pl->d_tiles, pl->d_blocks, pl->g);
   HIP_TRY(hipGetLastError());
   return SWCONV_OK;
 }
@@ -125,7 +134,7 @@ int launch_output_transform(const swconv_plan* pl, hipStream_t st, float* out) {
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, pl->dM, out, pl->g);
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, pl->dM, out, pl->d_tiles, pl->d_blocks, pl->g);
   HIP_TRY(hipGetLastError());
   return SWCONV_OK;
 }
@@ -157,6 +166,53 @@ int launch_stage(const swconv_plan* pl, hipStream_t st, int stage, const float* 
     case 0: return pl->m == 2 ? launch_input_transform<2>(pl, st, in) : launch_input_transform<4>(pl, st, in);
     case 1: return launch_spmm(pl, st);
     default: return pl->m == 2 ? launch_output_transform<2>(pl, st, out) : launch_output_transform<4>(pl, st, out);
+  }
+}
+
+// Index tables of the two transform kernels: where each tile and each (tile block, image) part
+// sits in the image and in a wave's LDS staging area.
+void build_transform_tables(swconv_plan* pl) {
+  const Geometry& g = pl->g;
+  const int m = pl->m, t = pl->t, nblk = g.Tp / 64;
+  TileInfo pad_tile;
+  pad_tile.in_org = 0;
+  pad_tile.yx0 = (int32_t)0x80008000u;  // y0 = x0 = -32768: nothing is inside the image
+  pad_tile.ylim = 0;
+  pad_tile.out_org = 0;
+  pl->tiles.assign((size_t)g.Tp, pad_tile);
+  BlockImage unused{};
+  unused.n = -1;
+  pl->blocks.assign((size_t)nblk * g.slots, unused);
+  for (int b = 0; b < nblk; ++b) {
+    const int tau0 = b * 64;
+    if (tau0 >= g.T) continue;
+    const int last = std::min(tau0 + 63, g.T - 1);
+    const int n_first = tau0 / g.tpi, n_last = last / g.tpi;
+    for (int n = n_first; n <= n_last; ++n) {
+      const int slot = n - n_first, base = n * g.tpi;
+      const int t_lo = std::max(tau0, base) - base, t_hi = std::min(last, base + g.tpi - 1) - base;
+      const int ty_lo = t_lo / g.tw, ty_hi = t_hi / g.tw;
+      const int y_lo = std::max(0, ty_lo * m - g.pad), y_hi = std::min(g.H, ty_hi * m - g.pad + t);
+      const int oy_lo = ty_lo * m, oy_hi = std::min(g.Ho, (ty_hi + 1) * m);
+      BlockImage& bi = pl->blocks[(size_t)b * g.slots + slot];
+      bi.n = n;
+      bi.in_elem0 = y_lo * g.W;
+      bi.in_span = (y_hi - y_lo) * g.W;
+      bi.out_elem0 = oy_lo * g.Wo;
+      bi.out_span = (oy_hi - oy_lo) * g.Wo;
+      bi.t_lo = t_lo;
+      bi.t_hi = t_hi;
+      bi.whole = (t_lo % g.tw == 0) && ((t_hi + 1) % g.tw == 0);
+      for (int tl = t_lo; tl <= t_hi; ++tl) {
+        const int ty = tl / g.tw, tx = tl % g.tw;
+        const int y0 = ty * m - g.pad, x0 = tx * m - g.pad;
+        TileInfo& ti = pl->tiles[(size_t)base + tl];
+        ti.in_org = slot * g.in_span - y_lo * g.W;
+        ti.yx0 = (int32_t)(((uint32_t)y0 & 0xffffu) | ((uint32_t)x0 << 16));
+        ti.ylim = (int32_t)((uint32_t)y_lo | ((uint32_t)(y_hi - 1) << 16));
+        ti.out_org = slot * g.out_span + (ty * m - oy_lo) * g.Wo + tx * m;
+      }
+    }
   }
 }
 
@@ -411,13 +467,25 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
     return SWCONV_EUNSUPPORTED;
   }
   pl->n_tau_blocks = (g.T + pl->tb - 1) / pl->tb;
+  if (H >= 32768 || W >= 32768) {  // 16-bit fields of the tile table
+    delete pl;
+    return SWCONV_EUNSUPPORTED;
+  }
+  g.wo_magic = (uint32_t)((((uint64_t)1 << 32) + g.Wo - 1) / g.Wo);
+  g.m_shift = m == 4 ? 2 : 1;
+  try {
+    build_transform_tables(pl);
+  } catch (const std::bad_alloc&) {
+    delete pl;
+    return SWCONV_ENOMEM;
+  }
   *out = pl;
   return SWCONV_OK;
 }
 
 void swconv_plan_destroy(swconv_plan* pl) {
   if (!pl) return;
-  void* bufs[] = {pl->dV, pl->dM, pl->d_stream, pl->d_slices, pl->d_items, pl->d_wg_begin, pl->d_wdense};
+  void* bufs[] = {pl->dV, pl->dM, pl->d_stream, pl->d_slices, pl->d_items, pl->d_wg_begin, pl->d_wdense, pl->d_tiles, pl->d_blocks};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
   delete pl;

@@ -26,6 +26,8 @@ struct Geometry {
   // and in each of them a run of at most `in_span` input / `out_span` output floats (whole rows)
   int slots, in_span, out_span;
   uint32_t v_bytes, m_bytes;  // sizes of the V and M workspaces (both below 4 GiB)
+  uint32_t wo_magic;          // ceil(2^32 / Wo): e / Wo == umulhi(e, wo_magic) for every staged element index
+  int m_shift;                // log2(m)
 };
 
 // V and M are addressed through buffer descriptors: address = base + scalar byte offset (the
@@ -47,21 +49,25 @@ __device__ __forceinline__ void buffer_store_f32x2(__amdgpu_buffer_rsrc_t r, uin
   __builtin_amdgcn_raw_buffer_store_b64(d, r, (int)voff, (int)soff, 0);
 }
 
-// The part of image n that a block of 64 consecutive tiles [tau0, last] covers.
-struct ImagePart {
-  int t_lo, t_hi;    // first / last tile of the block inside image n (image-local tile index)
-  int ty_lo, ty_hi;  // tile rows they span
+// Host-built index tables of the transform kernels (no integer division on the device).
+// Per tile (Tp entries; padding tiles have y0 = x0 = -32768 so that every pixel reads as zero):
+struct TileInfo {
+  int32_t in_org;   // staging-area float offset such that input pixel (y,x) sits at in_org + y*W + x
+  int32_t yx0;      // first input row y0 = ty*m - pad (low 16 bits, signed) and column x0 (high 16 bits)
+  int32_t ylim;     // first (low 16) and last (high 16) staged input row of the tile's image part
+  int32_t out_org;  // staging-area float offset of the tile's first output pixel
 };
-
-__device__ __forceinline__ ImagePart image_part(const Geometry& g, int n, int tau0, int last) {
-  ImagePart ip;
-  const int base = n * g.tpi;
-  ip.t_lo = max(tau0, base) - base;
-  ip.t_hi = min(last, base + g.tpi - 1) - base;
-  ip.ty_lo = ip.t_lo / g.tw;
-  ip.ty_hi = ip.t_hi / g.tw;
-  return ip;
-}
+// Per block of 64 consecutive tiles and image slot (Tp/64 * slots entries): the part of one
+// image the block covers.  n < 0 marks an unused slot.
+struct BlockImage {
+  int32_t n;          // image
+  int32_t in_elem0;   // first staged input element inside a channel plane (a whole row start)
+  int32_t in_span;    // staged input elements (whole rows)
+  int32_t out_elem0;  // first output element of the part inside an output plane (a whole row start)
+  int32_t out_span;   // output elements of the part (whole rows)
+  int32_t t_lo, t_hi; // first / last tile of the block inside the image (image-local tile index)
+  int32_t whole;      // 1 when the part consists of whole tile rows (every pixel of the span is owned)
+};
 
 // One slice = kSliceRows rows of one position's sparse matrix, rows sorted by length.  32 bytes,
 // so a wave fetches a whole descriptor with one scalar load.
@@ -93,13 +99,6 @@ __device__ __forceinline__ int xcd_contiguous_id(int bid, int nblocks) {
   return xcd * per + (xcd < rem ? xcd : rem) + local;
 }
 
-__device__ __forceinline__ void decode_tile(const Geometry& g, int tau, int& n, int& ty, int& tx) {
-  n = tau / g.tpi;
-  const int rem = tau - n * g.tpi;
-  ty = rem / g.tw;
-  tx = rem - ty * g.tw;
-}
-
 // ---------------------------------------------------------------------------------------------
 // Step 1: gather phi + V = B^T d B.  A wave owns one channel and 64 consecutive tiles: it copies
 // the input rows those tiles touch into its private LDS area with lane-contiguous (coalesced)
@@ -107,10 +106,12 @@ __device__ __forceinline__ void decode_tile(const Geometry& g, int tau, int& n, 
 // up to four images are all in flight before the first LDS write - then every lane gathers its
 // t x t tile from LDS (clamped addresses, all reads issued back to back, then selects zero what
 // lies outside the image), transforms it in registers and stores one value per position:
-// 64 lanes -> 256 contiguous bytes of V[p][c][.], addressed as wave-uniform base + lane.
+// 64 lanes -> 256 contiguous bytes of V[p][c][.], addressed as wave-uniform row + lane.
 // Block = 4 waves = 4 channels of the same tile block.
 template <int M>
 __global__ __launch_bounds__(256) void input_transform_kernel(const float* __restrict__ in, float* __restrict__ V,
+                                                              const TileInfo* __restrict__ tiles,
+                                                              const BlockImage* __restrict__ blocks,
                                                               const Geometry g) {
   constexpr int t = Wino<M>::t;
   extern __shared__ float stage[];
@@ -118,23 +119,23 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = blockIdx.y * 4 + wave;
   const int tau0 = blockIdx.x * 64;
-  const int last = min(tau0 + 63, g.T - 1);
-  const int n_first = tau0 / g.tpi, n_last = last / g.tpi;
   float* my = stage + wave * g.slots * g.in_span;
+  const BlockImage* bi = blocks + (size_t)blockIdx.x * g.slots;
+  const size_t plane = (size_t)g.H * g.W;
   if (c < g.C) {
     constexpr int IG = 4, EL = 4;  // images x loads per lane in flight
-    for (int n0 = n_first; n0 <= n_last; n0 += IG) {
+    for (int s0 = 0; s0 < g.slots; s0 += IG) {
       const float* src[IG];
       float* dst[IG];
       int span[IG], max_span = 0;
 #pragma unroll
       for (int i = 0; i < IG; ++i) {
-        const int n = min(n0 + i, n_last);
-        const ImagePart ip = image_part(g, n, tau0, last);
-        const int y_lo = max(0, ip.ty_lo * M - g.pad), y_hi = min(g.H, ip.ty_hi * M - g.pad + t);
-        span[i] = n0 + i <= n_last ? (y_hi - y_lo) * g.W : 0;
-        src[i] = in + (((size_t)n * g.C + c) * g.H + y_lo) * g.W;
-        dst[i] = my + (n - n_first) * g.in_span;
+        const int sidx = min(s0 + i, g.slots - 1);
+        const BlockImage b = bi[sidx];
+        const bool used = s0 + i < g.slots && b.n >= 0;
+        span[i] = used ? b.in_span : 0;
+        src[i] = in + ((size_t)max(b.n, 0) * g.C + c) * plane + b.in_elem0;
+        dst[i] = my + sidx * g.in_span;
         max_span = max(max_span, span[i]);
       }
       for (int e0 = 0; e0 < max_span; e0 += 64 * EL) {
@@ -158,28 +159,23 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
   }
   __syncthreads();
   if (c >= g.C) return;
-  const int tau = tau0 + lane;
   float d[t][t];
   {
-    const bool live = tau < g.T;
-    int n, ty, tx;
-    decode_tile(g, live ? tau : tau0, n, ty, tx);
-    const ImagePart ip = image_part(g, n, tau0, last);
-    const int y_lo = max(0, ip.ty_lo * M - g.pad), y_hi = min(g.H, ip.ty_hi * M - g.pad + t);
-    const float* img = my + (n - n_first) * g.in_span - y_lo * g.W;
-    const int y0 = ty * M - g.pad, x0 = tx * M - g.pad;
+    const TileInfo ti = tiles[tau0 + lane];
+    const int y0 = (int16_t)(ti.yx0 & 0xffff), x0 = ti.yx0 >> 16;
+    const int y_lo = ti.ylim & 0xffff, y_last = ti.ylim >> 16;
+    const float* img = my + ti.in_org;
     int xo[t];
     bool xok[t];
 #pragma unroll
     for (int j = 0; j < t; ++j) {
       const int x = x0 + j;
-      xok[j] = live && x >= 0 && x < g.W;
+      xok[j] = x >= 0 && x < g.W;
       xo[j] = min(max(x, 0), g.W - 1);
     }
 #pragma unroll
     for (int i = 0; i < t; ++i) {
-      const int y = y0 + i;
-      const float* row = img + min(max(y, y_lo), y_hi - 1) * g.W;  // a staged row in any case
+      const float* row = img + min(max(y0 + i, y_lo), y_last) * g.W;  // a staged row in any case
 #pragma unroll
       for (int j = 0; j < t; ++j) d[i][j] = row[xo[j]];
     }
@@ -387,7 +383,10 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
 // skipped.  Block = 4 waves = 4 output channels of the same tile block.
 template <int M>
 __global__ __launch_bounds__(256) void output_transform_kernel(const float* __restrict__ Mbuf,
-                                                               float* __restrict__ out, const Geometry g) {
+                                                               float* __restrict__ out,
+                                                               const TileInfo* __restrict__ tiles,
+                                                               const BlockImage* __restrict__ blocks,
+                                                               const Geometry g) {
   constexpr int t = Wino<M>::t;
   extern __shared__ float stage[];
   const int lane = threadIdx.x & 63;
@@ -395,11 +394,8 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
   const int k = blockIdx.y * 4 + wave;
   const int tau0 = blockIdx.x * 64;
   if (tau0 >= g.T) return;  // whole block is padding (uniform for the block)
-  const int last = min(tau0 + 63, g.T - 1);
-  const int n_first = tau0 / g.tpi, n_last = last / g.tpi;
-  const int tau = tau0 + lane;
   float* my = stage + wave * g.slots * g.out_span;
-  if (k < g.K && tau < g.T) {
+  if (k < g.K) {
     const __amdgpu_buffer_rsrc_t mr = make_rsrc(Mbuf, g.m_bytes);
     const uint32_t row0 = ((uint32_t)k * g.Tp + tau0) * 4u;        // wave-uniform byte offset, position 0
     const uint32_t pstride = (uint32_t)g.K * (uint32_t)g.Tp * 4u;  // bytes between positions
@@ -410,36 +406,34 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
       for (int j = 0; j < t; ++j) z[i][j] = buffer_load_f32(mr, lane * 4u, row0 + (i * t + j) * pstride);
     float y[M][M];
     output_transform<M>(z, y);
-    int n, ty, tx;
-    decode_tile(g, tau, n, ty, tx);
-    const ImagePart ip = image_part(g, n, tau0, last);
-    float* img = my + (n - n_first) * g.out_span - ip.ty_lo * M * g.Wo;
+    const TileInfo ti = tiles[tau0 + lane];
+    const int y0 = (int16_t)(ti.yx0 & 0xffff), x0 = ti.yx0 >> 16;
+    // rows / columns of the tile inside the output (<= 0 for a padding tile, whose y0 is -32768)
+    const int rows = y0 == -32768 ? 0 : g.Ho - (y0 + g.pad), cols = g.Wo - (x0 + g.pad);
+    float* px = my + ti.out_org;
 #pragma unroll
-    for (int a = 0; a < M; ++a) {
-      const int yy = ty * M + a;
+    for (int a = 0; a < M; ++a)
 #pragma unroll
-      for (int b = 0; b < M; ++b) {
-        const int xx = tx * M + b;
-        if (yy < g.Ho && xx < g.Wo) img[yy * g.Wo + xx] = y[a][b];
-      }
-    }
+      for (int b = 0; b < M; ++b)
+        if (a < rows && b < cols) px[a * g.Wo + b] = y[a][b];
   }
   __syncthreads();
   if (k >= g.K) return;
-  for (int n = n_first; n <= n_last; ++n) {
-    const ImagePart ip = image_part(g, n, tau0, last);
-    const int y_lo = ip.ty_lo * M, y_hi = min(g.Ho, (ip.ty_hi + 1) * M);
-    const int span = (y_hi - y_lo) * g.Wo;
-    const float* src = my + (n - n_first) * g.out_span;
-    float* dst = out + (((size_t)n * g.K + k) * g.Ho + y_lo) * g.Wo;
-    const bool whole_rows = (ip.t_lo % g.tw == 0) && ((ip.t_hi + 1) % g.tw == 0);
-    if (whole_rows) {
-      for (int e = lane; e < span; e += 64) dst[e] = src[e];
+  const BlockImage* bi = blocks + (size_t)blockIdx.x * g.slots;
+  const size_t plane = (size_t)g.Ho * g.Wo;
+  for (int sidx = 0; sidx < g.slots; ++sidx) {
+    const BlockImage b = bi[sidx];
+    if (b.n < 0) continue;
+    const float* src = my + sidx * g.out_span;
+    float* dst = out + ((size_t)b.n * g.K + k) * plane + b.out_elem0;
+    if (b.whole) {
+      for (int e = lane; e < b.out_span; e += 64) dst[e] = src[e];
     } else {
-      for (int e = lane; e < span; e += 64) {
-        const int ry = e / g.Wo, x = e - ry * g.Wo;
-        const int tl = ((y_lo + ry) / M) * g.tw + x / M;
-        if (tl >= ip.t_lo && tl <= ip.t_hi) dst[e] = src[e];
+      const int row_first = b.out_elem0 / g.Wo;  // wave-uniform
+      for (int e = lane; e < b.out_span; e += 64) {
+        const int ry = (int)__umulhi((uint32_t)e, g.wo_magic), x = e - ry * g.Wo;
+        const int tl = ((row_first + ry) >> g.m_shift) * g.tw + (x >> g.m_shift);
+        if (tl >= b.t_lo && tl <= b.t_hi) dst[e] = src[e];
       }
     }
   }
