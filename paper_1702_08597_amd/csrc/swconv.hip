@@ -460,8 +460,8 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   // LDS staging bounds of the transform kernels for any run of 64 consecutive tiles
   const int rows_t = (int)std::min<int64_t>(th, (64 + tw - 2) / tw + 1);
   g.slots = (int)std::min<int64_t>(N, (64 + g.tpi - 2) / g.tpi + 1);
-  g.in_span = std::min(H, rows_t * m + t - m) * W;
-  g.out_span = std::min(g.Ho, rows_t * m) * g.Wo;
+  g.in_span = (std::min(H, rows_t * m + t - m) * W + 63) / 64 * 64;
+  g.out_span = (std::min(g.Ho, rows_t * m) * g.Wo + 63) / 64 * 64;
   if ((int64_t)4 * g.slots * std::max(g.in_span, g.out_span) * (int64_t)sizeof(float) > kMaxLdsBytes) {
     delete pl;
     return SWCONV_EUNSUPPORTED;

@@ -23,7 +23,8 @@ struct Geometry {
   int T;                    // N*tpi
   int Tp;                   // padded tile count (row pitch of V and M)
   // LDS staging of the transforms: a block of 64 consecutive tiles touches at most `slots` images,
-  // and in each of them a run of at most `in_span` input / `out_span` output floats (whole rows)
+  // and in each of them a run of whole rows; `in_span` / `out_span` = pitch of one image slot in
+  // floats (the longest run, rounded up to a multiple of 64)
   int slots, in_span, out_span;
   uint32_t v_bytes, m_bytes;  // sizes of the V and M workspaces (both below 4 GiB)
   uint32_t wo_magic;          // ceil(2^32 / Wo): e / Wo == umulhi(e, wo_magic) for every staged element index
@@ -123,9 +124,12 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
   const BlockImage* bi = blocks + (size_t)blockIdx.x * g.slots;
   const size_t plane = (size_t)g.H * g.W;
   if (c < g.C) {
+    // Each image part is read through its own buffer descriptor (base = first staged element,
+    // size = the part's bytes): lanes past the end read zeros, so loads and LDS writes need no
+    // lane predicates; slots are pitched to a multiple of 64 floats to take the zero tail.
     constexpr int IG = 4, EL = 4;  // images x loads per lane in flight
     for (int s0 = 0; s0 < g.slots; s0 += IG) {
-      const float* src[IG];
+      __amdgpu_buffer_rsrc_t src[IG];
       float* dst[IG];
       int span[IG], max_span = 0;
 #pragma unroll
@@ -134,8 +138,8 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
         const BlockImage b = bi[sidx];
         const bool used = s0 + i < g.slots && b.n >= 0;
         span[i] = used ? b.in_span : 0;
-        src[i] = in + ((size_t)max(b.n, 0) * g.C + c) * plane + b.in_elem0;
-        dst[i] = my + sidx * g.in_span;
+        src[i] = make_rsrc(in + ((size_t)max(b.n, 0) * g.C + c) * plane + b.in_elem0, (uint32_t)span[i] * 4u);
+        dst[i] = my + sidx * g.in_span + lane;
         max_span = max(max_span, span[i]);
       }
       for (int e0 = 0; e0 < max_span; e0 += 64 * EL) {
@@ -143,17 +147,13 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
 #pragma unroll
         for (int i = 0; i < IG; ++i)
 #pragma unroll
-          for (int u = 0; u < EL; ++u) {
-            const int e = e0 + u * 64 + lane;
-            buf[i][u] = e < span[i] ? src[i][e] : 0.0f;
-          }
+          for (int u = 0; u < EL; ++u)
+            if (e0 + u * 64 < span[i]) buf[i][u] = buffer_load_f32(src[i], (lane + u * 64) * 4u, e0 * 4u);
 #pragma unroll
         for (int i = 0; i < IG; ++i)
 #pragma unroll
-          for (int u = 0; u < EL; ++u) {
-            const int e = e0 + u * 64 + lane;
-            if (e < span[i]) dst[i][e] = buf[i][u];
-          }
+          for (int u = 0; u < EL; ++u)
+            if (e0 + u * 64 < span[i]) dst[i][e0 + u * 64] = buf[i][u];
       }
     }
   }
@@ -201,10 +201,15 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
   const __amdgpu_buffer_rsrc_t vr = make_rsrc(V, g.v_bytes);
   const uint32_t row0 = ((uint32_t)c * g.Tp + tau0) * 4u;        // wave-uniform byte offset, position 0
   const uint32_t pstride = (uint32_t)g.C * (uint32_t)g.Tp * 4u;  // bytes between positions
+  uint32_t soff = row0;  // one scalar add per store
 #pragma unroll
   for (int i = 0; i < t; ++i)
 #pragma unroll
-    for (int j = 0; j < t; ++j) buffer_store_f32(vr, lane * 4u, row0 + (i * t + j) * pstride, v[i][j]);
+    for (int j = 0; j < t; ++j) {
+      buffer_store_f32(vr, lane * 4u, soff, v[i][j]);
+      soff += pstride;
+      asm volatile("" : "+s"(soff));
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -400,10 +405,15 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
     const uint32_t row0 = ((uint32_t)k * g.Tp + tau0) * 4u;        // wave-uniform byte offset, position 0
     const uint32_t pstride = (uint32_t)g.K * (uint32_t)g.Tp * 4u;  // bytes between positions
     float z[t][t];
+    uint32_t soff = row0;  // one scalar add per load
 #pragma unroll
     for (int i = 0; i < t; ++i)
 #pragma unroll
-      for (int j = 0; j < t; ++j) z[i][j] = buffer_load_f32(mr, lane * 4u, row0 + (i * t + j) * pstride);
+      for (int j = 0; j < t; ++j) {
+        z[i][j] = buffer_load_f32(mr, lane * 4u, soff);
+        soff += pstride;
+        asm volatile("" : "+s"(soff));
+      }
     float y[M][M];
     output_transform<M>(z, y);
     const TileInfo ti = tiles[tau0 + lane];
@@ -427,7 +437,9 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
     const float* src = my + sidx * g.out_span;
     float* dst = out + ((size_t)b.n * g.K + k) * plane + b.out_elem0;
     if (b.whole) {
-      for (int e = lane; e < b.out_span; e += 64) dst[e] = src[e];
+      // stores past the part's end are dropped by the descriptor: no lane predicate
+      const __amdgpu_buffer_rsrc_t orr = make_rsrc(dst, (uint32_t)b.out_span * 4u);
+      for (int e0 = 0; e0 < b.out_span; e0 += 64) buffer_store_f32(orr, lane * 4u, e0 * 4u, src[e0 + lane]);
     } else {
       const int row_first = b.out_elem0 / g.Wo;  // wave-uniform
       for (int e = lane; e < b.out_span; e += 64) {
