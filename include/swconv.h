@@ -65,7 +65,7 @@ const char* swconv_status_string(int status);
  * first swconv_set_weights / swconv_set_weights_dense on the then-current HIP device.
  * Errors: EINVAL for non-positive sizes, pad < 0, Ho or Wo < 1 or index ranges beyond int32;
  * EUNSUPPORTED for an unsupported (m,r) or a shape whose panels do not fit the kernels' LDS
- * budget (C > 640).  On success *out owns the plan; release with swconv_plan_destroy.
+ * budget (C > 639).  On success *out owns the plan; release with swconv_plan_destroy.
  */
 int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int m, int r, int pad);
 

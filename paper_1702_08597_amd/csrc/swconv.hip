@@ -19,6 +19,7 @@ using namespace swconv;
 namespace {
 
 constexpr int kMaxLdsBytes = 160 * 1024;
+constexpr int kSpmmLdsExtra = 64;    // the sparse product's slice counter sits behind the panel
 
 int env_int(const char* name, int dflt) {
   const char* s = std::getenv(name);
@@ -142,7 +143,7 @@ int launch_output_transform(const swconv_plan* pl, hipStream_t st, float* out) {
 template <int TPL, int NW>
 int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
   if (pl->n_wgs_used == 0) return SWCONV_OK;
-  const size_t lds = (size_t)pl->g.C * pl->tb * sizeof(float);
+  const size_t lds = (size_t)pl->g.C * pl->tb * sizeof(float) + kSpmmLdsExtra;
   auto kern = spmm_kernel<TPL, NW>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -244,16 +245,20 @@ U32* stream_slot(U32* stream, uint32_t group0, int32_t e) {
 
 // Static schedule of the sparse product.  The units (position, tile block, slice), in that order,
 // form one sequence; it is cut into one contiguous range per persistent workgroup such that every
-// range costs about the same: a slice costs its stream length plus a fixed overhead, shared out
-// over the waves, and entering a new panel costs one panel load.  The smallest feasible cost per
+// range costs about the same: a slice costs its stream length plus a fixed overhead, and entering
+// a new panel costs one panel load.  The smallest feasible cost per
 // range is found by bisection.  A range touches at most a few panels, consecutive ranges share
 // panels and weights (and, through xcd_contiguous_id, an XCD's L2), and the split adapts by
 // itself to positions of very different density.
 void build_schedule(swconv_plan* pl) {
-  const int P = pl->P, spp = pl->Kp / kSliceRows, ntb = pl->n_tau_blocks, nw = pl->waves;
-  // costs in units of one stream group processed by one wave
-  const int64_t slice_ovh = env_int("SWCONV_SPMM_SLICE_COST", 3);
-  const int64_t panel_cost = (int64_t)env_int("SWCONV_SPMM_PANEL_COST", 30) * nw;
+  const int P = pl->P, spp = pl->Kp / kSliceRows, ntb = pl->n_tau_blocks;
+  // Costs in units of the time a workgroup spends on one stream group (four LDS reads, about 13
+  // clocks with 16 waves).  Measured on MI355X: a slice costs about 160 clocks of workgroup time on
+  // top of its groups (descriptor and first stream fetch are scalar-memory round trips), staging a
+  // panel about 64 clocks per KiB.
+  const int64_t slice_ovh = env_int("SWCONV_SPMM_SLICE_COST", 12);
+  const int64_t panel_kib = ((int64_t)pl->g.C * pl->tb * (int64_t)sizeof(float) + 1023) / 1024;
+  const int64_t panel_cost = (int64_t)env_int("SWCONV_SPMM_PANEL_COST_PER_KIB", 5) * panel_kib;
   const int wgs_max = std::max(1, pl->n_wgs);
 
   auto cut = [&](int64_t budget, std::vector<WorkItem>* items, std::vector<int32_t>* begin) -> int {
@@ -423,13 +428,14 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   // Tile block of the sparse product.  Two tiles per lane (one 8-byte LDS read feeds two FMAs)
   // with the largest block TB <= 128, TB % 8 == 0, whose C x TB panel fits LDS - if that keeps
   // more than 32 lanes busy; else one tile per lane with TB = 64.
-  int tpl = 2, tb = (int)std::min<int64_t>(128, kMaxLdsBytes / ((int64_t)C * (int64_t)sizeof(float)) / 8 * 8);
+  const int64_t panel_budget = kMaxLdsBytes - kSpmmLdsExtra;
+  int tpl = 2, tb = (int)std::min<int64_t>(128, panel_budget / ((int64_t)C * (int64_t)sizeof(float)) / 8 * 8);
   const int force_tpl = env_int("SWCONV_SPMM_TPL", 0);
   if (tb <= 64 || force_tpl == 1) {
     tpl = 1;
     tb = 64;
   }
-  if ((int64_t)C * tb * (int64_t)sizeof(float) > kMaxLdsBytes) {
+  if ((int64_t)C * tb * (int64_t)sizeof(float) > panel_budget) {
     delete pl;
     return SWCONV_EUNSUPPORTED;
   }

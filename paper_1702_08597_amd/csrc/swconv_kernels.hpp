@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
 // maps to r under xcd_contiguous_id, so neighbouring ranges - which share panels and weights -
 // share an XCD's L2.  A range is a short list of work items (runs of slices of one panel).  For an
 // item the workgroup stages the C x TB panel V[p][:, tau_block] in LDS (unless it is already
-// there), then the waves take the item's slices round-robin.
+// there), then the waves draw the item's slices from a shared counter, longest first.
 //
 // A slice's stream is a sequence of 8-dword groups; a group holds kGroupSlots slots, a slot one
 // (panel row byte offset, weight) pair for each of the slice's kSliceRows rows.  Per batch of
@@ -257,7 +257,8 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
                                                            const int32_t* __restrict__ wg_begin, int n_wgs, int C,
                                                            int K, int Tp, int TB, uint32_t m_bytes) {
   constexpr int NT = NWAVES * 64;
-  extern __shared__ float panel[];  // [C][TB], at LDS offset 0 of the workgroup
+  extern __shared__ float panel[];  // [C][TB], at LDS offset 0 of the workgroup, then the slice counter
+  int* next_slice = reinterpret_cast<int*>(panel + (size_t)C * TB);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int range = xcd_contiguous_id(blockIdx.x, n_wgs);
@@ -300,17 +301,22 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
         *reinterpret_cast<float4*>(panel + base * 4) =
             *reinterpret_cast<const float4*>(src + (size_t)row * Tp + q * 4);
       }
+      if (threadIdx.x == 0) *next_slice = it.slice_begin + NWAVES;
       __syncthreads();
     }
 
+    // Waves take slices dynamically, longest first (rows are sorted by length): the first one by
+    // wave number, every further one from a counter in LDS, so a wave that drew short slices
+    // simply draws more of them.  The next slice is drawn - and its descriptor fetched - before
+    // the current one is computed.
     int s = it.slice_begin + wave;
     if (s >= it.slice_end) continue;
     Slice sl = slices[s];
     while (true) {
-      // descriptor of this wave's next slice, fetched while the current one is computed (the
-      // index is clamped, so the load is unconditional and in bounds)
-      const int s_next = s + NWAVES;
-      const Slice sl_next = slices[min(s_next, n_slices - 1)];
+      int drawn = 0;
+      if (lane == 0) drawn = __hip_atomic_fetch_add(next_slice, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      const int s_next = __builtin_amdgcn_readfirstlane(drawn);
+      const Slice sl_next = slices[min(s_next, n_slices - 1)];  // clamped: unconditional, in bounds
       const uint32_t* sp = stream + (size_t)sl.group0 * 8;
       float acc[kSliceRows][TPL];
 #pragma unroll

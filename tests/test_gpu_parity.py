@@ -82,7 +82,7 @@ SMALL = [
     (1, 1, 1, 1, 1, 2, 1),     # one pixel, one tile
     (1, 2, 3, 3, 3, 4, 0),     # Ho = 1
     (70, 4, 4, 4, 4, 4, 1),    # one tile per image, many images
-    (1, 640, 6, 6, 2, 2, 1),   # largest channel count the panel holds
+    (1, 639, 6, 6, 2, 2, 1),   # largest channel count the panel holds
 ]
 
 
