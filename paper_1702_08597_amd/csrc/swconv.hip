@@ -152,7 +152,8 @@ int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
   }
   hipLaunchKernelGGL(kern, dim3(pl->n_wgs_used), dim3(NW * 64), lds, st, pl->dV, pl->dM, pl->d_stream, pl->d_slices,
                      (int)pl->slices.size(), pl->d_items, pl->d_wg_begin, pl->n_wgs_used, pl->g.C, pl->g.K, pl->g.Tp,
-                     pl->tb, pl->g.m_bytes);
+                     pl->tb, pl->g.m_bytes, pl->g.v_bytes,
+                     (uint32_t)((((uint64_t)1 << 32) + pl->tb / 4 - 1) / (pl->tb / 4)));
   HIP_TRY(hipGetLastError());
   return SWCONV_OK;
 }

@@ -219,8 +219,9 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
 // into one contiguous, equal-cost range per workgroup; range r is run by the workgroup whose id
 // maps to r under xcd_contiguous_id, so neighbouring ranges - which share panels and weights -
 // share an XCD's L2.  A range is a short list of work items (runs of slices of one panel).  For an
-// item the workgroup stages the C x TB panel V[p][:, tau_block] in LDS (unless it is already
-// there), then the waves draw the item's slices from a shared counter, longest first.
+// item the workgroup stages the C x TB panel V[p][:, tau_block] in LDS - the panel of the next
+// item is already on its way into registers while the current one is computed - then the waves
+// draw the item's slices from a shared counter, longest first.
 //
 // A slice's stream is a sequence of 8-dword groups; a group holds kGroupSlots slots, a slot one
 // (panel row byte offset, weight) pair for each of the slice's kSliceRows rows.  Per batch of
@@ -234,6 +235,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
 // panel operand is read with ds_read_addtid_b32, whose address is M0 + 4 * lane: the row offset
 // goes from its scalar register straight into M0 and no vector address arithmetic is spent.
 constexpr int kBatchGroups = 8;  // 8-dword groups fetched per scalar-memory round trip
+constexpr int kPanelPieces = 10;  // 16-byte panel pieces a thread holds in registers
 
 // Four panel reads for four wave-uniform row offsets.  One wait state is required between the
 // write of M0 and an LDS add-TID instruction (s_nop 0).  The loads are complete on return.
@@ -255,7 +257,8 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
                                                            const Slice* __restrict__ slices, int n_slices,
                                                            const WorkItem* __restrict__ items,
                                                            const int32_t* __restrict__ wg_begin, int n_wgs, int C,
-                                                           int K, int Tp, int TB, uint32_t m_bytes) {
+                                                           int K, int Tp, int TB, uint32_t m_bytes,
+                                                           uint32_t v_bytes, uint32_t v4_magic) {
   constexpr int NT = NWAVES * 64;
   extern __shared__ float panel[];  // [C][TB], at LDS offset 0 of the workgroup, then the slice counter
   int* next_slice = reinterpret_cast<int*>(panel + (size_t)C * TB);
@@ -263,7 +266,6 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int range = xcd_contiguous_id(blockIdx.x, n_wgs);
   const int item_begin = wg_begin[range], item_end = wg_begin[range + 1];
-  int cur_p = -1, cur_tb = -1;
   // TPL = 2: lane l owns the adjacent tiles 2l, 2l+1 of the block and reads them with one 8-byte
   // LDS access; when TB < 128 the lanes past TB/2 idle (they read lane 0's words, store nothing)
   const bool lane_active = TPL == 1 || 2 * lane < TB;
@@ -271,39 +273,42 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
   const __amdgpu_buffer_rsrc_t mr = make_rsrc(Mbuf, m_bytes);
   const uint32_t m_lane_off = lane_active ? lane * TPL * 4u : 0xfffffff0u;
 
+  // Panel staging.  Thread i moves the 16-byte pieces i, i + NT, ... of a panel; their offsets
+  // inside a panel are the same for every item, so they are computed once.  The pieces of the
+  // NEXT item's panel are fetched into registers right after the current panel is in LDS and stay
+  // in flight while the current item is computed; at the switch they only have to be written to
+  // LDS.  (kPanelPieces * NT * 16 bytes covers the largest panel LDS can hold.)
+  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  const int v4_per_row = TB / 4, total = C * v4_per_row;
+  const __amdgpu_buffer_rsrc_t vr = make_rsrc(V, v_bytes);
+  uint32_t voff[kPanelPieces];
+#pragma unroll
+  for (int u = 0; u < kPanelPieces; ++u) {
+    const int idx = threadIdx.x + u * NT;
+    const int row = (int)__umulhi((uint32_t)idx, v4_magic), q = idx - row * v4_per_row;
+    voff[u] = idx < total ? ((uint32_t)row * Tp + q * 4) * 4u : 0xfffffff0u;  // past the end: reads 0
+  }
+  u32x4_t piece[kPanelPieces];
+  auto fetch_panel = [&](const WorkItem& w) {
+    const uint32_t soff = ((uint32_t)w.p * C * Tp + (uint32_t)w.tau_block * TB) * 4u;
+#pragma unroll
+    for (int u = 0; u < kPanelPieces; ++u)
+      if (u * NT < total) piece[u] = __builtin_amdgcn_raw_buffer_load_b128(vr, (int)voff[u], (int)soff, 0);
+  };
+  if (item_begin < item_end) fetch_panel(items[item_begin]);
+
   for (int item = item_begin; item < item_end; ++item) {
     const WorkItem it = items[item];
     const int tau0 = it.tau_block * TB;
-    if (it.p != cur_p || it.tau_block != cur_tb) {  // uniform for the workgroup
-      cur_p = it.p;
-      cur_tb = it.tau_block;
-      __syncthreads();  // every wave is done reading the previous panel
-      // stage the panel: rows of TB floats, 16 bytes per lane, all of a lane's loads in flight
-      // before its first LDS write
-      const float* src = V + ((size_t)it.p * C) * Tp + tau0;
-      const int V4_PER_ROW = TB / 4;
-      constexpr int U = 8;
-      const int total = C * V4_PER_ROW;
-      int base = threadIdx.x;
-      for (; base + (U - 1) * NT < total; base += NT * U) {  // full batches, no bounds checks
-        float4 buf[U];
+    __syncthreads();  // every wave is done reading the previous panel
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int idx = base + u * NT;
-          const int row = idx / V4_PER_ROW, q = idx - row * V4_PER_ROW;
-          buf[u] = *reinterpret_cast<const float4*>(src + (size_t)row * Tp + q * 4);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) *reinterpret_cast<float4*>(panel + (base + u * NT) * 4) = buf[u];
-      }
-      for (; base < total; base += NT) {
-        const int row = base / V4_PER_ROW, q = base - row * V4_PER_ROW;
-        *reinterpret_cast<float4*>(panel + base * 4) =
-            *reinterpret_cast<const float4*>(src + (size_t)row * Tp + q * 4);
-      }
-      if (threadIdx.x == 0) *next_slice = it.slice_begin + NWAVES;
-      __syncthreads();
+    for (int u = 0; u < kPanelPieces; ++u) {
+      const int idx = threadIdx.x + u * NT;
+      if (idx < total) *reinterpret_cast<u32x4_t*>(panel + idx * 4) = piece[u];
     }
+    if (threadIdx.x == 0) *next_slice = it.slice_begin + NWAVES;
+    __syncthreads();
+    if (item + 1 < item_end) fetch_panel(items[item + 1]);
 
     // Waves take slices dynamically, longest first (rows are sorted by length): the first one by
     // wave number, every further one from a counter in LDS, so a wave that drew short slices
