@@ -21,6 +21,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
 FP32_VECTOR_TFLOPS = 157.3  # MI355X fp32 vector, published (256 CU x 128 FMA lanes x 2 x 2.4 GHz)
 STAGES = ("input_transform_kernel", "spmm_kernel", "output_transform_kernel")
+# HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain
+# copy of known size (profiles/pmc_traffic_alexnet_conv3_n32_f4.md); known for the default workload only.
+MEASURED_TRAFFIC = {
+    ("alexnet_conv3_n32_f4", 0.10): {"input_transform_kernel": 24.52e6, "spmm_kernel": 54.66e6,
+                                     "output_transform_kernel": 36.69e6},
+}
 
 
 def stage_models(cfg, nnz):
@@ -43,6 +49,9 @@ def main():
     ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--dense", action="store_true", help="time the 0%%-sparsity MFMA comparison path instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="instead of the benchmark, run 20 plain device copies of this many MiB (a kernel of known "
+                         "HBM traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the forward path has no multi-GPU part); "
@@ -54,6 +63,17 @@ def main():
 
     from paper_1702_08597_amd import binding as sw
     from paper_1702_08597_amd import synth
+
+    if args.copy_calibration > 0:
+        n = args.copy_calibration * (1 << 20) // 4
+        a = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        b = torch.empty_like(a)
+        for _ in range(20):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_MiB": args.copy_calibration, "copies": 20,
+                          "bytes_read_per_copy": n * 4, "bytes_written_per_copy": n * 4}))
+        return
 
     name = args.workload or synth.BENCH_CONFIG
     cfg, x, rp, ci, va = synth.make_layer(name, density=args.density)
@@ -124,7 +144,8 @@ def main():
         else:
             roof = {"bound": "alu", "achieved": d["TFLOPs"], "peak": FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(d["TFLOPs"] / FP32_VECTOR_TFLOPS, 4)}
-        roof.update({"kernel": d["kernel"], "avg_ms": d["ms"], "traffic": None})
+        traffic = MEASURED_TRAFFIC.get((name, 0.10 if args.density is None else args.density), {}).get(d["kernel"])
+        roof.update({"kernel": d["kernel"], "avg_ms": d["ms"], "traffic": traffic})
         result["roofline"] = roof
         result["stages"] = stages
         st = sw.swconv_plan_weight_stats(plan)
