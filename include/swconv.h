@@ -82,8 +82,8 @@ void swconv_plan_destroy(swconv_plan* plan);
  *           legal and are treated as non-zeros.  nnz = 0 is legal (colidx/vals may be NULL).
  * The arrays are validated, re-packed into the kernels' sliced layout (rows of a position
  * sorted by length, grouped four at a time, padded with zero weights) together with a
- * static, cost-balanced schedule for the persistent workgroups of the sparse product, and copied to the device before the call returns; the caller keeps
- * ownership of its arrays.  May be called again with a new pattern.  Blocks the host.
+ * static, cost-balanced schedule for the persistent workgroups of the sparse product, and copied
+ * to the device before the call returns; the caller keeps ownership of its arrays.  May be called again with a new pattern.  Blocks the host.
  * Errors: EINVAL on any CSR violation (the plan keeps its previous weights); ENOMEM; EHIP when
  * no device is usable - the host-side packed copy is still kept in that case, so
  * swconv_debug_export_weights works without a GPU.
@@ -140,6 +140,14 @@ int swconv_debug_copy_M(swconv_plan* plan, float* M_host);
  * Errors: ESTATE when no sparse weights were set.
  */
 int swconv_debug_export_weights(swconv_plan* plan, int32_t* rowptr, int32_t* colidx, float* vals);
+
+/*
+ * Verifies the static schedule of the sparse product on the host: every (position, tile block,
+ * slice) unit is assigned to exactly one persistent workgroup and no launched workgroup is idle.
+ * Returns SWCONV_OK, or SWCONV_EINVAL when the schedule is not a partition; ESTATE when no sparse
+ * weights were set.  Needs no GPU.
+ */
+int swconv_debug_check_schedule(const swconv_plan* plan);
 
 /*
  * Sizes derived by the plan (any pointer may be NULL): positions P, tiles T, Ho, Wo.

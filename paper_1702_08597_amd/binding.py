@@ -16,7 +16,7 @@ EXPORTS = [
     "swconv_status_string", "swconv_plan_create", "swconv_plan_destroy", "swconv_set_weights",
     "swconv_forward", "swconv_set_weights_dense", "swconv_forward_dense", "swconv_profile_forward",
     "swconv_debug_copy_V", "swconv_debug_copy_M", "swconv_debug_export_weights", "swconv_plan_sizes",
-    "swconv_plan_weight_stats",
+    "swconv_plan_weight_stats", "swconv_debug_check_schedule",
 ]
 
 _lib = None
@@ -55,6 +55,7 @@ def lib():
                                         ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.swconv_plan_weight_stats.argtypes = [_vp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
                                                ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int64)]
+        L.swconv_debug_check_schedule.argtypes = [_vp]
         _lib = L
     return _lib
 
@@ -134,6 +135,11 @@ def swconv_plan_weight_stats(plan):
     _check(lib().swconv_plan_weight_stats(plan, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d)),
            "swconv_plan_weight_stats")
     return dict(nnz=a.value, padded_nnz=b.value, work_items=c.value, max_item=d.value)
+
+
+def swconv_debug_check_schedule(plan):
+    """Raises unless the sparse product's static schedule covers every unit exactly once."""
+    _check(lib().swconv_debug_check_schedule(plan), "swconv_debug_check_schedule")
 
 
 def swconv_debug_copy_V(plan, C):

