@@ -432,7 +432,10 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   const int64_t panel_budget = kMaxLdsBytes - kSpmmLdsExtra;
   int tpl = 2, tb = (int)std::min<int64_t>(128, panel_budget / ((int64_t)C * (int64_t)sizeof(float)) / 8 * 8);
   const int force_tpl = env_int("SWCONV_SPMM_TPL", 0);
-  if (tb <= 64 || force_tpl == 1) {
+  // LDS instructions per non-zero are proportional to the number of tile blocks: take two tiles
+  // per lane only if that needs fewer blocks than one tile per lane with TB = 64
+  const bool one_fits = (int64_t)C * 64 * (int64_t)sizeof(float) <= panel_budget;
+  if (tb <= 64 || force_tpl == 1 || (one_fits && force_tpl != 2 && (T + tb - 1) / tb >= (T + 63) / 64)) {
     tpl = 1;
     tb = 64;
   }
