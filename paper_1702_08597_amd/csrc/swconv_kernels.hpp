@@ -463,16 +463,19 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
     if (b.n < 0) continue;
     const float* src = my + sidx * g.out_span;
     float* dst = out + ((size_t)b.n * g.K + k) * plane + b.out_elem0;
+    // stores past the part's end are dropped by the descriptor: no lane predicate
+    const __amdgpu_buffer_rsrc_t orr = make_rsrc(dst, (uint32_t)b.out_span * 4u);
     if (b.whole) {
-      // stores past the part's end are dropped by the descriptor: no lane predicate
-      const __amdgpu_buffer_rsrc_t orr = make_rsrc(dst, (uint32_t)b.out_span * 4u);
-      for (int e0 = 0; e0 < b.out_span; e0 += 64) buffer_store_f32<SWCONV_AUX_OUT>(orr, lane * 4u, e0 * 4u, src[e0 + lane]);
+      for (int e0 = 0; e0 < b.out_span; e0 += 64)
+        buffer_store_f32<SWCONV_AUX_OUT>(orr, lane * 4u, e0 * 4u, src[e0 + lane]);
     } else {
       const int row_first = b.out_elem0 / g.Wo;  // wave-uniform
-      for (int e = lane; e < b.out_span; e += 64) {
+      for (int e0 = 0; e0 < b.out_span; e0 += 64) {
+        const int e = e0 + lane;
         const int ry = (int)__umulhi((uint32_t)e, g.wo_magic), x = e - ry * g.Wo;
         const int tl = ((row_first + ry) >> g.m_shift) * g.tw + (x >> g.m_shift);
-        if (tl >= b.t_lo && tl <= b.t_hi) dst[e] = src[e];
+        const bool mine = tl >= b.t_lo && tl <= b.t_hi;  // a pixel of a tile of this block
+        buffer_store_f32<SWCONV_AUX_OUT>(orr, mine ? lane * 4u : 0xfffffff0u, e0 * 4u, src[e]);
       }
     }
   }
