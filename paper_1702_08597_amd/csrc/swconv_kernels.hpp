@@ -316,7 +316,7 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
   for (int item = item_begin; item < item_end; ++item) {
     const WorkItem it = items[item];
     const int tau0 = it.tau_block * TB;
-    __syncthreads();  // every wave is done reading the previous panel
+    if (item != item_begin) __syncthreads();  // every wave is done reading the previous panel
 #pragma unroll
     for (int u = 0; u < kPanelPieces; ++u) {
       const int idx = threadIdx.x + u * NT;
