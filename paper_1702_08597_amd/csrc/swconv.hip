@@ -55,8 +55,6 @@ int upload(T** dptr, const std::vector<T>& h) {
 struct swconv_plan {
   Geometry g{};
   int m = 0, r = 0, t = 0, P = 0;
-  int tpl = 1;   // tiles per lane in the sparse product
-  int tb = 64;   // tile block = 64 * tpl
   int waves = 8; // waves per workgroup in the sparse product
   int Kp = 0;    // K rounded up to a multiple of the slice height
   int Kq = 0;    // K rounded up to the dense GEMM's row tile
@@ -65,7 +63,7 @@ struct swconv_plan {
   // host-side packed sparse weights
   bool have_sparse = false;
   int64_t nnz = 0, padded_nnz = 0, max_item = 0;
-  std::vector<uint32_t> stream;      // 8-dword groups of (row offset, weight) slots
+  std::vector<uint32_t> stream;      // 512-byte batches of (row offset, weight) pairs
   std::vector<Slice> slices;         // P * Kp / kSliceRows
   std::vector<int32_t> sorted_rows;  // P * Kp: original row k of each sorted row, -1 = padding
   std::vector<int32_t> sorted_len;   // P * Kp: stored entries of each sorted row
@@ -140,27 +138,26 @@ int launch_output_transform(const swconv_plan* pl, hipStream_t st, float* out) {
   return SWCONV_OK;
 }
 
-template <int TPL, int NW>
+template <int NW>
 int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
   if (pl->n_wgs_used == 0) return SWCONV_OK;
-  const size_t lds = (size_t)pl->g.C * pl->tb * sizeof(float) + kSpmmLdsExtra;
-  auto kern = spmm_kernel<TPL, NW>;
+  const size_t lds = (size_t)pl->g.C * kTileBlock * sizeof(float) + kSpmmLdsExtra;
+  auto kern = spmm_kernel<NW>;
   static bool attr_set = false;
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(pl->n_wgs_used), dim3(NW * 64), lds, st, pl->dV, pl->dM, pl->d_stream, pl->d_slices,
-                     (int)pl->slices.size(), pl->d_items, pl->d_wg_begin, pl->n_wgs_used, pl->g.C, pl->g.K, pl->g.Tp,
-                     pl->tb, pl->g.m_bytes, pl->g.v_bytes,
-                     (uint32_t)((((uint64_t)1 << 32) + pl->tb / 4 - 1) / (pl->tb / 4)));
+  hipLaunchKernelGGL(kern, dim3(pl->n_wgs_used), dim3(NW * 64), lds, st, pl->dV, pl->dM, pl->d_stream,
+                     (uint32_t)(pl->stream.size() * sizeof(uint32_t)), pl->d_slices, (int)pl->slices.size(),
+                     pl->d_items, pl->d_wg_begin, pl->n_wgs_used, pl->g.C, pl->g.K, pl->g.Tp, pl->g.m_bytes,
+                     pl->g.v_bytes);
   HIP_TRY(hipGetLastError());
   return SWCONV_OK;
 }
 
 int launch_spmm(const swconv_plan* pl, hipStream_t st) {
-  if (pl->tpl == 2) return pl->waves == 16 ? launch_spmm_t<2, 16>(pl, st) : launch_spmm_t<2, 8>(pl, st);
-  return pl->waves == 16 ? launch_spmm_t<1, 16>(pl, st) : launch_spmm_t<1, 8>(pl, st);
+  return pl->waves == 16 ? launch_spmm_t<16>(pl, st) : launch_spmm_t<8>(pl, st);
 }
 
 int launch_stage(const swconv_plan* pl, hipStream_t st, int stage, const float* in, float* out) {
@@ -238,12 +235,6 @@ int validate_csr(const swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   return SWCONV_OK;
 }
 
-// Slot e of a slice that starts at 8-dword group `group0`: 2 * kSliceRows dwords, offsets first.
-template <typename U32>
-U32* stream_slot(U32* stream, uint32_t group0, int32_t e) {
-  return stream + (size_t)group0 * 8 + (size_t)e * 2 * kSliceRows;
-}
-
 // Static schedule of the sparse product.  The units (position, tile block, slice), in that order,
 // form one sequence; it is cut into one contiguous range per persistent workgroup such that every
 // range costs about the same: a slice costs its stream length plus a fixed overhead, and entering
@@ -253,13 +244,13 @@ U32* stream_slot(U32* stream, uint32_t group0, int32_t e) {
 // itself to positions of very different density.
 void build_schedule(swconv_plan* pl) {
   const int P = pl->P, spp = pl->Kp / kSliceRows, ntb = pl->n_tau_blocks;
-  // Costs in units of the time a workgroup spends on one stream group (four LDS reads, about 13
-  // clocks with 16 waves).  Measured on MI355X: a slice costs about 160 clocks of workgroup time on
-  // top of its groups (descriptor and first stream fetch are scalar-memory round trips), staging a
-  // panel about 64 clocks per KiB.
-  const int64_t slice_ovh = env_int("SWCONV_SPMM_SLICE_COST", 12);
-  const int64_t panel_kib = ((int64_t)pl->g.C * pl->tb * (int64_t)sizeof(float) + 1023) / 1024;
-  const int64_t panel_cost = (int64_t)env_int("SWCONV_SPMM_PANEL_COST_PER_KIB", 5) * panel_kib;
+  // Costs in units of the time a workgroup spends on one step of a slice (four 16-byte LDS reads
+  // per wave quarter-row, 16 FMAs per lane).  Fitted on MI355X over uniform and skewed patterns: a
+  // slice costs about 32 steps on top of its own (draw, descriptor, first batches, row store),
+  // staging a panel about 20 steps per KiB.
+  const int64_t slice_ovh = env_int("SWCONV_SPMM_SLICE_COST", 32);
+  const int64_t panel_kib = ((int64_t)pl->g.C * kTileBlock * (int64_t)sizeof(float) + 1023) / 1024;
+  const int64_t panel_cost = (int64_t)env_int("SWCONV_SPMM_PANEL_COST_PER_KIB", 20) * panel_kib;
   const int wgs_max = std::max(1, pl->n_wgs);
 
   auto cut = [&](int64_t budget, std::vector<WorkItem>* items, std::vector<int32_t>* begin) -> int {
@@ -312,11 +303,17 @@ void build_schedule(swconv_plan* pl) {
   pl->n_wgs_used = cut(lo, &pl->items, &pl->wg_begin);
   pl->max_item = 0;
   for (int b = 0; b < pl->n_wgs_used; ++b) {
-    int64_t groups = 0;
+    int64_t steps = 0;
     for (int i = pl->wg_begin[b]; i < pl->wg_begin[b + 1]; ++i)
-      for (int sidx = pl->items[i].slice_begin; sidx < pl->items[i].slice_end; ++sidx) groups += pl->slices[sidx].len;
-    pl->max_item = std::max(pl->max_item, groups * 4);
+      for (int sidx = pl->items[i].slice_begin; sidx < pl->items[i].slice_end; ++sidx) steps += pl->slices[sidx].len;
+    pl->max_item = std::max(pl->max_item, steps * kSliceRows);
   }
+}
+
+// Dword index of the (offset, weight) pair of row q, step e of a slice whose first 512-byte batch
+// is `batch0`: lane (q, e % 16) of batch e / 16.
+inline size_t stream_entry(uint32_t batch0, int q, int32_t e) {
+  return ((size_t)batch0 + (size_t)(e / kBatchSteps)) * 128 + ((size_t)q * kBatchSteps + (size_t)(e % kBatchSteps)) * 2;
 }
 
 // Re-pack per-position CSR into the sliced layout and build the schedule.
@@ -329,7 +326,8 @@ void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx,
   pl->slices.assign((size_t)P * slices_per_pos, Slice{});
 
   std::vector<int32_t> order(K);
-  uint64_t group_cursor = 0;
+  uint64_t cursor = 0;  // 512-byte batches
+  pl->padded_nnz = 0;
   for (int p = 0; p < P; ++p) {
     const int32_t* rp = rowptr + (int64_t)p * K;
     std::iota(order.begin(), order.end(), 0);
@@ -343,18 +341,21 @@ void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx,
       Slice& sl = pl->slices[(size_t)p * slices_per_pos + s];
       sl.p = p;
       sl.row0 = p * Kp + s * kSliceRows;
-      // rows are sorted: the first is the longest; whole groups of kGroupSlots slots
-      sl.len = (pl->sorted_len[sl.row0] + kGroupSlots - 1) / kGroupSlots;
-      sl.group0 = (uint32_t)group_cursor;
-      for (int r = 0; r < 4; ++r) sl.k[r] = r < kSliceRows ? pl->sorted_rows[sl.row0 + r] : -1;
-      group_cursor += sl.len;
+      sl.batch0 = (uint32_t)cursor;
+      for (int r = 0; r < kSliceRows; ++r) sl.k[r] = pl->sorted_rows[sl.row0 + r];
+      // rows are sorted: the first is the longest; whole groups of steps
+      sl.len = (pl->sorted_len[sl.row0] + kStepGroup - 1) / kStepGroup * kStepGroup;
+      cursor += (sl.len + kBatchSteps - 1) / kBatchSteps;
+      pl->padded_nnz += (int64_t)sl.len * kSliceRows;
     }
   }
-  pl->padded_nnz = (int64_t)group_cursor * 4;
-  // a slot entry is (byte offset of the panel row of column c, weight); padding = row 0,
-  // weight +0.0f; one spare batch at the end keeps the kernel's whole-batch fetches in bounds
-  const uint32_t row_bytes = (uint32_t)pl->tb * sizeof(float);
-  pl->stream.assign(((size_t)group_cursor + kBatchGroups) * 8, 0u);
+  // an entry is (byte offset of the panel row of column c, weight); padding = row 0, weight +0.0f.
+  // The kernel addresses the stream with 32-bit byte offsets and fetches up to two batches past a
+  // slice's end: two spare batches keep even those inside the allocation.
+  cursor += 2;
+  if (cursor * 512 >= ((uint64_t)1 << 32) - 4096) throw std::bad_alloc();
+  const uint32_t row_bytes = (uint32_t)kTileBlock * sizeof(float);
+  pl->stream.assign((size_t)cursor * 128, 0u);
   for (size_t s = 0; s < pl->slices.size(); ++s) {
     const Slice& sl = pl->slices[s];
     const int32_t* rp = rowptr + (int64_t)sl.p * K;
@@ -363,9 +364,9 @@ void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx,
       if (k < 0) continue;
       const int32_t q0 = rp[k], len = rp[k + 1] - rp[k];
       for (int32_t e = 0; e < len; ++e) {
-        uint32_t* slot = stream_slot(pl->stream.data(), sl.group0, e);
-        slot[r] = (uint32_t)colidx[q0 + e] * row_bytes;
-        std::memcpy(&slot[kSliceRows + r], &vals[q0 + e], sizeof(float));
+        uint32_t* entry = &pl->stream[stream_entry(sl.batch0, r, e)];
+        entry[0] = (uint32_t)colidx[q0 + e] * row_bytes;
+        std::memcpy(&entry[1], &vals[q0 + e], sizeof(float));
       }
     }
   }
@@ -426,20 +427,10 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
 
   swconv_plan* pl = new (std::nothrow) swconv_plan();
   if (!pl) return SWCONV_ENOMEM;
-  // Tile block of the sparse product.  Two tiles per lane (one 8-byte LDS read feeds two FMAs)
-  // with the largest block TB <= 128, TB % 8 == 0, whose C x TB panel fits LDS - if that keeps
-  // more than 32 lanes busy; else one tile per lane with TB = 64.
+  // the sparse product stages a C x 64 panel (256 bytes per channel) plus its slice counter in LDS
   const int64_t panel_budget = kMaxLdsBytes - kSpmmLdsExtra;
-  int tpl = 2, tb = (int)std::min<int64_t>(128, panel_budget / ((int64_t)C * (int64_t)sizeof(float)) / 8 * 8);
-  const int force_tpl = env_int("SWCONV_SPMM_TPL", 0);
-  // LDS instructions per non-zero are proportional to the number of tile blocks: take two tiles
-  // per lane only if that needs fewer blocks than one tile per lane with TB = 64
-  const bool one_fits = (int64_t)C * 64 * (int64_t)sizeof(float) <= panel_budget;
-  if (tb <= 64 || force_tpl == 1 || (one_fits && force_tpl != 2 && (T + tb - 1) / tb >= (T + 63) / 64)) {
-    tpl = 1;
-    tb = 64;
-  }
-  if ((int64_t)C * tb * (int64_t)sizeof(float) > panel_budget) {
+  const int64_t panel_bytes = (int64_t)C * kTileBlock * (int64_t)sizeof(float);
+  if (panel_bytes > panel_budget) {
     delete pl;
     return SWCONV_EUNSUPPORTED;
   }
@@ -447,21 +438,19 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   pl->r = r;
   pl->t = t;
   pl->P = P;
-  pl->tpl = tpl;
-  // one workgroup per CU when the panel takes more than half of LDS: then 16 waves, else 8
-  const int dflt_waves = (int64_t)C * tb * (int64_t)sizeof(float) * 2 > kMaxLdsBytes ? 16 : 8;
+  // two workgroups of 8 waves per CU while two panels fit LDS, else one of 16
+  const int dflt_waves = panel_bytes * 2 + 2 * kSpmmLdsExtra > kMaxLdsBytes ? 16 : 8;
   pl->waves = env_int("SWCONV_SPMM_WAVES", dflt_waves) == 16 ? 16 : 8;
   // a thread stages at most kPanelPieces 16-byte pieces of a panel
-  if ((int64_t)C * tb * (int64_t)sizeof(float) > (int64_t)kPanelPieces * pl->waves * 64 * 16) pl->waves = 16;
-  pl->tb = tb;
+  if (panel_bytes > (int64_t)kPanelPieces * pl->waves * 64 * 16) pl->waves = 16;
   pl->Kp = (K + kSliceRows - 1) / kSliceRows * kSliceRows;
   Geometry& g = pl->g;
   g.N = N; g.C = C; g.H = H; g.W = W; g.K = K; g.pad = pad;
   g.Ho = (int)Ho; g.Wo = (int)Wo; g.th = (int)th; g.tw = (int)tw; g.tpi = (int)(th * tw);
   g.T = (int)T;
-  // row pitch of V and M: whole tile blocks of the sparse product, and a multiple of 128 for the
-  // transform kernels (64-tile blocks) and the dense comparison GEMM (128-tile blocks)
-  g.Tp = (int)(((T + tb - 1) / tb * tb + 127) / 128 * 128);
+  // row pitch of V and M: whole 64-tile blocks (transforms, sparse product) and a multiple of 128
+  // for the dense comparison GEMM
+  g.Tp = (int)((T + 127) / 128 * 128);
   // V and M are addressed with 32-bit byte offsets (buffer descriptors)
   if ((int64_t)P * std::max(C, K) * g.Tp * (int64_t)sizeof(float) >= ((int64_t)1 << 32) - 256) {
     delete pl;
@@ -478,7 +467,7 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
     delete pl;
     return SWCONV_EUNSUPPORTED;
   }
-  pl->n_tau_blocks = (g.T + pl->tb - 1) / pl->tb;
+  pl->n_tau_blocks = (g.T + kTileBlock - 1) / kTileBlock;
   if (H >= 32768 || W >= 32768) {  // 16-bit fields of the tile table
     delete pl;
     return SWCONV_EUNSUPPORTED;
@@ -516,7 +505,7 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
       cus = prop.multiProcessorCount;
     else
       (void)hipGetLastError();
-    const size_t panel_bytes = (size_t)pl->g.C * pl->tb * sizeof(float);
+    const size_t panel_bytes = (size_t)pl->g.C * kTileBlock * sizeof(float) + kSpmmLdsExtra;
     const int per_cu = std::max<int>(1, std::min<int>(32 / pl->waves, (int)(kMaxLdsBytes / panel_bytes)));
     pl->n_wgs = std::max(1, env_int("SWCONV_SPMM_WGS", cus * per_cu));
   }
@@ -613,9 +602,9 @@ int swconv_debug_export_weights(swconv_plan* pl, int32_t* rowptr, int32_t* colid
       if (k < 0) continue;
       const int32_t q0 = rowptr[(int64_t)sl.p * K + k];
       for (int32_t e = 0; e < pl->sorted_len[sl.row0 + r]; ++e) {
-        const uint32_t* slot = stream_slot(pl->stream.data(), sl.group0, e);
-        colidx[q0 + e] = (int32_t)(slot[r] / ((uint32_t)pl->tb * sizeof(float)));
-        std::memcpy(&vals[q0 + e], &slot[kSliceRows + r], sizeof(float));
+        const uint32_t* entry = &pl->stream[stream_entry(sl.batch0, r, e)];
+        colidx[q0 + e] = (int32_t)(entry[0] / ((uint32_t)kTileBlock * sizeof(float)));
+        std::memcpy(&vals[q0 + e], &entry[1], sizeof(float));
       }
     }
   return SWCONV_OK;

@@ -47,7 +47,8 @@ struct Geometry {
 
 // V and M are addressed through buffer descriptors: address = base + scalar byte offset (the
 // row, wave-uniform) + vector byte offset (the lane), so a row access costs no vector address
-// arithmetic; accesses past `bytes` are dropped by the hardware.
+// arithmetic.  An access whose vector + scalar offset reaches past `bytes` is dropped by the
+// hardware (loads return 0); on gfx950 the scalar offset takes part in that check (measured).
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
@@ -89,11 +90,11 @@ struct BlockImage {
 // One slice = kSliceRows rows of one position's sparse matrix, rows sorted by length.  32 bytes,
 // so a wave fetches a whole descriptor with one scalar load.
 struct Slice {
-  uint32_t group0;  // first 8-dword group of the slice in the packed stream
-  int32_t len;      // groups in the slice (4 (row offset, weight) pairs each)
+  uint32_t batch0;  // first 512-byte batch of the slice in the packed stream
+  int32_t len;      // steps in the slice (one (row offset, weight) pair per row each), a multiple of kStepGroup
   int32_t row0;     // index of its first row in the host's sorted-row table (P * Kp entries)
   int32_t p;        // position
-  int32_t k[4];     // output channel of each row (first kSliceRows entries), -1 = padding row
+  int32_t k[4];     // output channel of each row, -1 = padding row
 };
 
 // One unit of the schedule: a contiguous run of slices of one position, for one tile block.
@@ -104,8 +105,11 @@ struct WorkItem {
   int32_t slice_end;    // one past the last slice
 };
 
-constexpr int kSliceRows = 2;   // rows per slice
-constexpr int kGroupSlots = 4 / kSliceRows;  // slots (one pair per row) in an 8-dword stream group
+constexpr int kSliceRows = 4;    // rows per slice = quarters of a wave
+constexpr int kTileBlock = 64;   // tiles per panel row: 16 lanes of a quarter x 4 tiles
+constexpr int kBatchSteps = 16;  // steps per 512-byte stream batch (one per lane of a quarter)
+constexpr int kStepGroup = 4;    // steps issued together; a slice's length is a multiple of it
+constexpr int kPanelPieces = 10; // 16-byte panel pieces a thread holds in registers
 constexpr int kXcds = 8;
 
 // Workgroup ids are dealt round-robin to the 8 XCDs; remap them so that each XCD gets one
@@ -235,87 +239,142 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
 // into one contiguous, equal-cost range per workgroup; range r is run by the workgroup whose id
 // maps to r under xcd_contiguous_id, so neighbouring ranges - which share panels and weights -
 // share an XCD's L2.  A range is a short list of work items (runs of slices of one panel).  For an
-// item the workgroup stages the C x TB panel V[p][:, tau_block] in LDS - the panel of the next
-// item is already on its way into registers while the current one is computed - then the waves
-// draw the item's slices from a shared counter, longest first.
+// item the workgroup stages the C x 64 panel V[p][:, tau_block] in LDS, then the waves draw the
+// item's slices from a shared counter, longest first.
 //
-// A slice's stream is a sequence of 8-dword groups; a group holds kGroupSlots slots, a slot one
-// (panel row byte offset, weight) pair for each of the slice's kSliceRows rows.  Per batch of
-// eight groups the wave fetches 64 dwords with four back-to-back wave-uniform (scalar) loads;
-// weights stay in scalar registers, there is one vector accumulator per row and tile.
+// Lanes <-> tiles (Section 5: vectorise over tiles), four tiles per lane and four rows per wave:
+// a slice has four rows and each quarter of a wave (16 lanes) works on one of them.  Lane (q, s)
+// owns row q and the tiles 4s .. 4s+3 of the 64-tile block, so one 16-byte LDS read per lane
+// feeds four FMAs, and one address addition serves four non-zeros x 64 tiles: 5 vector-ALU
+// instructions per 256 tile-FMAs.  That matters because the vector ALU (one wave instruction per
+// SIMD per 4 clocks) and LDS (a 16-byte-per-lane read per 4.8 clocks per CU, whether the quarters
+// read one row or four different ones) are both close to saturated by this loop.
+// The (row offset, weight) pairs differ between the quarters, so they travel through vector
+// memory, 16 steps per load: lane (q, s) fetches the pair of row q, step 16 b + s, and at step i
+// every lane of a quarter takes the pair from lane i of its quarter with a DPP row broadcast,
+// folded into the address addition and into the FMAs.
 //
-// LDS is the binding unit: a CU retires one LDS instruction per 4 clocks whatever its width up to
-// 8 bytes per lane (5.3 clocks for 16 bytes), so the kernel reads two tiles per lane with one
-// 8-byte access (TPL = 2, tile block TB <= 128 chosen so that the panel fits LDS) wherever that
-// feeds more FMAs per LDS instruction than one tile per lane does.  With TPL = 1 (TB = 64) the
-// panel operand is read with ds_read_addtid_b32, whose address is M0 + 4 * lane: the row offset
-// goes from its scalar register straight into M0 and no vector address arithmetic is spent.
-constexpr int kBatchGroups = 8;  // 8-dword groups fetched per scalar-memory round trip
-constexpr int kPanelPieces = 10;  // 16-byte panel pieces a thread holds in registers
+// Stream layout: per slice, batches of 512 bytes; batch b holds [q][s] -> (offset, weight) of row
+// q, step 16 b + s; rows shorter than the slice are padded with (0, +0.0f).  A slice's length is
+// a multiple of kStepGroup steps.  Panel rows are 64 tiles = 256 bytes.
 
-// Four panel reads for four wave-uniform row offsets.  One wait state is required between the
-// write of M0 and an LDS add-TID instruction (s_nop 0).  The loads are complete on return.
-__device__ __forceinline__ void panel_read4(const uint32_t (&off)[4], float (&x)[4]) {
-  asm volatile(
-      "s_mov_b32 m0, %4\n s_nop 0\n ds_read_addtid_b32 %0\n"
-      "s_mov_b32 m0, %5\n s_nop 0\n ds_read_addtid_b32 %1\n"
-      "s_mov_b32 m0, %6\n s_nop 0\n ds_read_addtid_b32 %2\n"
-      "s_mov_b32 m0, %7\n s_nop 0\n ds_read_addtid_b32 %3\n"
-      "s_waitcnt lgkmcnt(0)"
-      : "=&v"(x[0]), "=&v"(x[1]), "=&v"(x[2]), "=&v"(x[3])
-      : "s"(off[0]), "s"(off[1]), "s"(off[2]), "s"(off[3])
-      : "memory");
+template <int I>
+__device__ __forceinline__ uint32_t quarter_bcast(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x150 + I, 0xf, 0xf, true);  // row_newbcast:I
 }
 
-template <int TPL, int NWAVES>
-__global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restrict__ V, float* __restrict__ Mbuf,
-                                                           const uint32_t* __restrict__ stream,
-                                                           const Slice* __restrict__ slices, int n_slices,
-                                                           const WorkItem* __restrict__ items,
-                                                           const int32_t* __restrict__ wg_begin, int n_wgs, int C,
-                                                           int K, int Tp, int TB, uint32_t m_bytes,
-                                                           uint32_t v_bytes, uint32_t v4_magic) {
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4v_t __attribute__((ext_vector_type(4)));
+
+// acc += w * x with w taken from lane I of the lane's quarter.  The broadcast rides on the FMAs
+// themselves (DPP operand); the compiler would spend a separate move on it.  `bw` is only ever
+// written by a memory load, and FIRST puts two wait states in front, so the rule "two wait states
+// between a vector-ALU write of a register and a DPP read of it" holds whatever precedes the group.
+template <int I, bool FIRST>
+__device__ __forceinline__ void quarter_fma(f32x4_t& acc, uint32_t bw, const f32x4_t& x) {
+#define SWCONV_QFMA(N)                                                                         \
+  "v_fmac_f32_dpp %0, %4, %5 row_newbcast:" #N " row_mask:0xf bank_mask:0xf\n"                 \
+  "v_fmac_f32_dpp %1, %4, %6 row_newbcast:" #N " row_mask:0xf bank_mask:0xf\n"                 \
+  "v_fmac_f32_dpp %2, %4, %7 row_newbcast:" #N " row_mask:0xf bank_mask:0xf\n"                 \
+  "v_fmac_f32_dpp %3, %4, %8 row_newbcast:" #N " row_mask:0xf bank_mask:0xf"
+#define SWCONV_QFMA_CASE(N)                                                                    \
+  if constexpr (I == N) {                                                                      \
+    if constexpr (FIRST)                                                                       \
+      asm("s_nop 1\n" SWCONV_QFMA(N)                                                           \
+          : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])                             \
+          : "v"(bw), "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]));                              \
+    else                                                                                       \
+      asm(SWCONV_QFMA(N)                                                                       \
+          : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])                             \
+          : "v"(bw), "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]));                              \
+  }
+  SWCONV_QFMA_CASE(0) SWCONV_QFMA_CASE(1) SWCONV_QFMA_CASE(2) SWCONV_QFMA_CASE(3)
+  SWCONV_QFMA_CASE(4) SWCONV_QFMA_CASE(5) SWCONV_QFMA_CASE(6) SWCONV_QFMA_CASE(7)
+  SWCONV_QFMA_CASE(8) SWCONV_QFMA_CASE(9) SWCONV_QFMA_CASE(10) SWCONV_QFMA_CASE(11)
+  SWCONV_QFMA_CASE(12) SWCONV_QFMA_CASE(13) SWCONV_QFMA_CASE(14) SWCONV_QFMA_CASE(15)
+#undef SWCONV_QFMA_CASE
+#undef SWCONV_QFMA
+}
+
+// Steps G*kStepGroup .. +kStepGroup-1 of the batch held in (boff, bw): the four panel reads
+// are issued back to back, the FMAs follow as the data arrives.
+template <int G>
+__device__ __forceinline__ void quarter_group(const float* panel, uint32_t lane_sub, uint32_t boff, uint32_t bw,
+                                              f32x4_t& acc) {
+  constexpr int I0 = G * kStepGroup;
+  static_assert(kStepGroup == 4, "four steps per group");
+  const char* base = reinterpret_cast<const char*>(panel);
+  const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 0>(boff) + lane_sub));
+  const f32x4_t x1 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 1>(boff) + lane_sub));
+  const f32x4_t x2 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 2>(boff) + lane_sub));
+  const f32x4_t x3 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 3>(boff) + lane_sub));
+  quarter_fma<I0 + 0, true>(acc, bw, x0);
+  quarter_fma<I0 + 1, false>(acc, bw, x1);
+  quarter_fma<I0 + 2, false>(acc, bw, x2);
+  quarter_fma<I0 + 3, false>(acc, bw, x3);
+}
+
+// The first `steps` (a positive multiple of kStepGroup, wave-uniform) steps of one batch.
+__device__ __forceinline__ void quarter_batch(const float* panel, uint32_t lane_sub, const u32x2_t& b, int steps,
+                                              f32x4_t& acc) {
+  quarter_group<0>(panel, lane_sub, b.x, b.y, acc);
+  if (steps > 1 * kStepGroup) quarter_group<1>(panel, lane_sub, b.x, b.y, acc);
+  if (steps > 2 * kStepGroup) quarter_group<2>(panel, lane_sub, b.x, b.y, acc);
+  if (steps > 3 * kStepGroup) quarter_group<3>(panel, lane_sub, b.x, b.y, acc);
+}
+
+template <int NWAVES>
+__global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(
+    const float* __restrict__ V, float* __restrict__ Mbuf, const uint32_t* __restrict__ stream, uint32_t stream_bytes,
+    const Slice* __restrict__ slices, int n_slices, const WorkItem* __restrict__ items,
+    const int32_t* __restrict__ wg_begin, int n_wgs, int C, int K, int Tp, uint32_t m_bytes, uint32_t v_bytes) {
   constexpr int NT = NWAVES * 64;
-  extern __shared__ float panel[];  // [C][TB], at LDS offset 0 of the workgroup, then the slice counter
+  constexpr int TB = kTileBlock;
+  extern __shared__ float panel[];  // [C][64], at LDS offset 0 of the workgroup, then the slice counter
   int* next_slice = reinterpret_cast<int*>(panel + (size_t)C * TB);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int range = xcd_contiguous_id(blockIdx.x, n_wgs);
   const int item_begin = wg_begin[range], item_end = wg_begin[range + 1];
-  // TPL = 2: lane l owns the adjacent tiles 2l, 2l+1 of the block and reads them with one 8-byte
-  // LDS access; when TB < 128 the lanes past TB/2 idle (they read lane 0's words, store nothing)
-  const bool lane_active = TPL == 1 || 2 * lane < TB;
-  const float* lane_panel = panel + (lane_active ? lane * TPL : 0);
+  const int quarter = lane >> 4;
+  const uint32_t lane_sub = (uint32_t)(lane & 15) * 16u;  // byte offset of the lane's four tiles in a row
   const __amdgpu_buffer_rsrc_t mr = make_rsrc(Mbuf, m_bytes);
-  const uint32_t m_lane_off = lane_active ? lane * TPL * 4u : 0xfffffff0u;
+  const __amdgpu_buffer_rsrc_t sr = make_rsrc(stream, stream_bytes);
+  const uint32_t lane8 = (uint32_t)lane * 8u;
 
-  // Panel staging.  Thread i moves the 16-byte pieces i, i + NT, ... of a panel; their offsets
-  // inside a panel are the same for every item, so they are computed once.  The pieces of the
-  // NEXT item's panel are fetched into registers right after the current panel is in LDS and stay
-  // in flight while the current item is computed; at the switch they only have to be written to
-  // LDS.  (kPanelPieces * NT * 16 bytes covers the largest panel LDS can hold.)
+  // Panel staging: thread i moves the 16-byte pieces i, i + NT, ... of a panel; their offsets
+  // inside a panel are the same for every item, so they are computed once.  The next item's panel
+  // travels through registers.  Vector-memory results come back in issue order and the stream
+  // batches use the same path, so a wave asks for the next panel only after its last slice of the
+  // item: a wait on a batch never has a panel load in front of it.  (Surplus pieces are parked
+  // past the end of the buffer and read 0 without touching memory.)
   typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-  const int v4_per_row = TB / 4, total = C * v4_per_row;
+  constexpr int v4_per_row = TB / 4;
+  const int total = C * v4_per_row;
   const __amdgpu_buffer_rsrc_t vr = make_rsrc(V, v_bytes);
   uint32_t voff[kPanelPieces];
 #pragma unroll
   for (int u = 0; u < kPanelPieces; ++u) {
     const int idx = threadIdx.x + u * NT;
-    const int row = (int)__umulhi((uint32_t)idx, v4_magic), q = idx - row * v4_per_row;
-    voff[u] = idx < total ? ((uint32_t)row * Tp + q * 4) * 4u : 0xfffffff0u;  // past the end: reads 0
+    const int row = idx / v4_per_row, q = idx % v4_per_row;
+    voff[u] = idx < total ? ((uint32_t)row * Tp + q * 4) * 4u : 0xfffffff0u;
   }
   u32x4_t piece[kPanelPieces];
   auto fetch_panel = [&](const WorkItem& w) {
     const uint32_t soff = ((uint32_t)w.p * C * Tp + (uint32_t)w.tau_block * TB) * 4u;
 #pragma unroll
     for (int u = 0; u < kPanelPieces; ++u)
-      if (u * NT < total) piece[u] = __builtin_amdgcn_raw_buffer_load_b128(vr, (int)voff[u], (int)soff, 0);
+      piece[u] = __builtin_amdgcn_raw_buffer_load_b128(vr, (int)voff[u], (int)soff, 0);
+  };
+  auto load_batch = [&](uint32_t byte_off) -> u32x2_t {
+    return __builtin_amdgcn_raw_buffer_load_b64(sr, (int)lane8, (int)byte_off, 0);  // past the end: reads 0
   };
   if (item_begin < item_end) fetch_panel(items[item_begin]);
 
   for (int item = item_begin; item < item_end; ++item) {
     const WorkItem it = items[item];
     const int tau0 = it.tau_block * TB;
+    const bool has_next = item + 1 < item_end;
     if (item != item_begin) __syncthreads();  // every wave is done reading the previous panel
 #pragma unroll
     for (int u = 0; u < kPanelPieces; ++u) {
@@ -324,82 +383,50 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(const float* __restri
     }
     if (threadIdx.x == 0) *next_slice = it.slice_begin + NWAVES;
     __syncthreads();
-    if (item + 1 < item_end) fetch_panel(items[item + 1]);
 
-    // Waves take slices dynamically, longest first (rows are sorted by length): the first one by
-    // wave number, every further one from a counter in LDS, so a wave that drew short slices
-    // simply draws more of them.  The next slice is drawn - and its descriptor fetched - before
-    // the current one is computed.
+    // Waves take slices dynamically, longest first: the first one by wave number, every further
+    // one from a counter in LDS.  The next slice is drawn before the current one is computed, its
+    // first two batches are fetched before the current one's result is stored.
     int s = it.slice_begin + wave;
-    if (s >= it.slice_end) continue;
+    if (s >= it.slice_end) {
+      if (has_next) fetch_panel(items[item + 1]);
+      continue;
+    }
     Slice sl = slices[s];
+    u32x2_t b0 = load_batch(sl.batch0 * 512u), b1 = load_batch(sl.batch0 * 512u + 512u);
     while (true) {
       int drawn = 0;
       if (lane == 0) drawn = __hip_atomic_fetch_add(next_slice, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
       const int s_next = __builtin_amdgcn_readfirstlane(drawn);
       const Slice sl_next = slices[min(s_next, n_slices - 1)];  // clamped: unconditional, in bounds
-      const uint32_t* sp = stream + (size_t)sl.group0 * 8;
-      float acc[kSliceRows][TPL];
-#pragma unroll
-      for (int r = 0; r < kSliceRows; ++r)
-#pragma unroll
-        for (int e = 0; e < TPL; ++e) acc[r][e] = 0.0f;
-      // one batch = kBatchGroups groups = 64 dwords fetched with four back-to-back scalar loads,
-      // so the scalar-memory latency is paid once per 32 (offset, weight) pairs; the stream
-      // carries one spare batch at its end, so the fetch of a short last batch stays in bounds
-      for (int remaining = sl.len; remaining > 0; remaining -= kBatchGroups, sp += 8 * kBatchGroups) {
-        // the empty asm statement pins all four loads in scalar registers here, so the compiler
-        // cannot sink each load next to its (conditional) use and pay the latency four times
-        typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
-        static_assert(kBatchGroups == 8, "batch = four 16-dword fetches");
-        u32x16 q[4];
-        q[0] = *reinterpret_cast<const u32x16*>(sp);
-        q[1] = *reinterpret_cast<const u32x16*>(sp + 16);
-        q[2] = *reinterpret_cast<const u32x16*>(sp + 32);
-        q[3] = *reinterpret_cast<const u32x16*>(sp + 48);
-        asm volatile("" : "+s"(q[0]), "+s"(q[1]), "+s"(q[2]), "+s"(q[3]));
-#pragma unroll
-        for (int g = 0; g < kBatchGroups; ++g) {  // one group = four non-zeros
-          if (g < remaining) {                    // wave-uniform
-            // dword layout of a group: per slot, kSliceRows offsets then kSliceRows weights
-            uint32_t off[4];
-            float w[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int slot = e / kSliceRows, r = e % kSliceRows;
-              const int d = (g & 1) * 8 + slot * 2 * kSliceRows + r;
-              off[e] = q[g >> 1][d];
-              w[e] = __uint_as_float(q[g >> 1][d + kSliceRows]);
-            }
-            if constexpr (TPL == 1) {
-              float x[4];
-              panel_read4(off, x);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) acc[e % kSliceRows][0] = fmaf(w[e], x[e], acc[e % kSliceRows][0]);
-            } else {
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const float2 v2 = *reinterpret_cast<const float2*>(
-                    reinterpret_cast<const char*>(lane_panel) + off[e]);
-                acc[e % kSliceRows][0] = fmaf(w[e], v2.x, acc[e % kSliceRows][0]);
-                acc[e % kSliceRows][1] = fmaf(w[e], v2.y, acc[e % kSliceRows][1]);
-              }
-            }
-          }
-        }
+      const bool more = s_next < it.slice_end;
+      f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+      // Two batch registers in turn: batch j of a slice sits in register j % 2.  A register is
+      // refilled right after its batch is consumed, unconditionally, with the batch two ahead - or,
+      // when the slice has no such batch, with batch 0 / 1 of the NEXT slice (parked past the end
+      // of the stream when there is none: reads 0, touches no memory).  So the batches of a
+      // slice are always on their way one or two batches of work before they are needed, and no
+      // wait in the loop ever has more than one younger load in front of it.
+      const uint32_t base = sl.batch0 * 512u, next_base = more ? sl_next.batch0 * 512u : 0xfffff000u;
+      const int batches = (sl.len + kBatchSteps - 1) / kBatchSteps;
+      for (int j = 0, remaining = sl.len; j < batches; j += 2, remaining -= 2 * kBatchSteps) {
+        quarter_batch(panel, lane_sub, b0, remaining, acc);
+        b0 = load_batch(j + 2 < batches ? base + (uint32_t)(j + 2) * 512u : next_base);
+        if (j + 1 < batches) quarter_batch(panel, lane_sub, b1, remaining - kBatchSteps, acc);
+        b1 = load_batch(j + 3 < batches ? base + (uint32_t)(j + 3) * 512u : next_base + 512u);
       }
-#pragma unroll
-      for (int r = 0; r < kSliceRows; ++r) {
-        const int k = sl.k[r];
-        if (k >= 0) {  // wave-uniform; idle lanes are parked beyond the buffer, their store is dropped
-          const uint32_t row = (((uint32_t)it.p * K + k) * Tp + tau0) * 4u;
-          if constexpr (TPL == 1)
-            buffer_store_f32<SWCONV_AUX_M>(mr, m_lane_off, row, acc[r][0]);
-          else
-            buffer_store_f32x2<SWCONV_AUX_M>(mr, m_lane_off, row, acc[r][0], acc[r][1]);
-        }
+      if (batches == 0) {  // an all-empty slice consumed nothing: fetch the next slice's batches here
+        b0 = load_batch(next_base);
+        b1 = load_batch(next_base + 512u);
       }
-      if (s_next >= it.slice_end) break;
+      // row of this lane's quarter; quarters of padding rows are parked beyond the buffer
+      const int k = quarter == 0 ? sl.k[0] : quarter == 1 ? sl.k[1] : quarter == 2 ? sl.k[2] : sl.k[3];
+      const uint32_t moff = k >= 0 ? (((uint32_t)it.p * K + (uint32_t)k) * Tp + tau0) * 4u + lane_sub : 0xfffffff0u;
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v_t, acc), mr, (int)moff, 0, SWCONV_AUX_M);
+      if (!more) {
+        if (has_next) fetch_panel(items[item + 1]);
+        break;
+      }
       s = s_next;
       sl = sl_next;
     }
