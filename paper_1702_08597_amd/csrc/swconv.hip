@@ -69,6 +69,7 @@ struct swconv_plan {
   std::vector<int32_t> sorted_len;   // P * Kp: stored entries of each sorted row
   std::vector<WorkItem> items;       // in range order
   std::vector<int32_t> wg_begin;     // n_wgs_used + 1 offsets into items, one range per workgroup
+  std::vector<RangeHeader> ranges;   // the same, as the kernel reads it
   int n_wgs = 512;                   // persistent workgroups the device can hold at once
   int n_wgs_used = 0;                // workgroups the current schedule uses
 
@@ -84,7 +85,7 @@ struct swconv_plan {
   uint32_t* d_stream = nullptr;
   Slice* d_slices = nullptr;
   WorkItem* d_items = nullptr;
-  int32_t* d_wg_begin = nullptr;
+  RangeHeader* d_ranges = nullptr;
   float* d_wdense = nullptr;  // [P][C][Kq]
 };
 
@@ -150,7 +151,7 @@ int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
   }
   hipLaunchKernelGGL(kern, dim3(pl->n_wgs_used), dim3(NW * 64), lds, st, pl->dV, pl->dM, pl->d_stream,
                      (uint32_t)(pl->stream.size() * sizeof(uint32_t)), pl->d_slices, (int)pl->slices.size(),
-                     pl->d_items, pl->d_wg_begin, pl->n_wgs_used, pl->g.C, pl->g.K, pl->g.Tp, pl->g.m_bytes,
+                     pl->d_items, pl->d_ranges, pl->n_wgs_used, pl->g.C, pl->g.K, pl->g.Tp, pl->g.m_bytes,
                      pl->g.v_bytes);
   HIP_TRY(hipGetLastError());
   return SWCONV_OK;
@@ -301,6 +302,13 @@ void build_schedule(swconv_plan* pl) {
     if (cut(mid, nullptr, nullptr) <= wgs_max) hi = mid; else lo = mid + 1;
   }
   pl->n_wgs_used = cut(lo, &pl->items, &pl->wg_begin);
+  pl->ranges.assign((size_t)pl->n_wgs_used, RangeHeader{});
+  for (int b = 0; b < pl->n_wgs_used; ++b) {
+    RangeHeader& h = pl->ranges[b];
+    h.item_begin = pl->wg_begin[b];
+    h.item_end = pl->wg_begin[b + 1];
+    h.first = pl->items[h.item_begin];
+  }
   pl->max_item = 0;
   for (int b = 0; b < pl->n_wgs_used; ++b) {
     int64_t steps = 0;
@@ -381,7 +389,7 @@ int upload_sparse(swconv_plan* pl) {
   if ((rc = upload(&pl->d_stream, pl->stream))) return rc;
   if ((rc = upload(&pl->d_slices, pl->slices))) return rc;
   if ((rc = upload(&pl->d_items, pl->items))) return rc;
-  if ((rc = upload(&pl->d_wg_begin, pl->wg_begin))) return rc;
+  if ((rc = upload(&pl->d_ranges, pl->ranges))) return rc;
   HIP_TRY(hipDeviceSynchronize());
   pl->sparse_on_device = true;
   return SWCONV_OK;
@@ -486,7 +494,7 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
 
 void swconv_plan_destroy(swconv_plan* pl) {
   if (!pl) return;
-  void* bufs[] = {pl->dV, pl->dM, pl->d_stream, pl->d_slices, pl->d_items, pl->d_wg_begin, pl->d_wdense, pl->d_tiles, pl->d_blocks};
+  void* bufs[] = {pl->dV, pl->dM, pl->d_stream, pl->d_slices, pl->d_items, pl->d_ranges, pl->d_wdense, pl->d_tiles, pl->d_blocks};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
   delete pl;

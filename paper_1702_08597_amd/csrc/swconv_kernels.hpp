@@ -105,6 +105,14 @@ struct WorkItem {
   int32_t slice_end;    // one past the last slice
 };
 
+// What a persistent workgroup needs to start, in one 32-byte scalar load: its range of work
+// items and the first of them.
+struct RangeHeader {
+  int32_t item_begin, item_end;  // indices into the work-item list; never empty for a launched workgroup
+  WorkItem first;                // = items[item_begin]
+  int32_t pad[2];
+};
+
 constexpr int kSliceRows = 4;    // rows per slice = quarters of a wave
 constexpr int kTileBlock = 64;   // tiles per panel row: 16 lanes of a quarter x 4 tiles
 constexpr int kBatchSteps = 16;  // steps per 512-byte stream batch (one per lane of a quarter)
@@ -327,15 +335,14 @@ template <int NWAVES>
 __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(
     const float* __restrict__ V, float* __restrict__ Mbuf, const uint32_t* __restrict__ stream, uint32_t stream_bytes,
     const Slice* __restrict__ slices, int n_slices, const WorkItem* __restrict__ items,
-    const int32_t* __restrict__ wg_begin, int n_wgs, int C, int K, int Tp, uint32_t m_bytes, uint32_t v_bytes) {
+    const RangeHeader* __restrict__ ranges, int n_wgs, int C, int K, int Tp, uint32_t m_bytes, uint32_t v_bytes) {
   constexpr int NT = NWAVES * 64;
   constexpr int TB = kTileBlock;
   extern __shared__ float panel[];  // [C][64], at LDS offset 0 of the workgroup, then the slice counter
   int* next_slice = reinterpret_cast<int*>(panel + (size_t)C * TB);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int range = xcd_contiguous_id(blockIdx.x, n_wgs);
-  const int item_begin = wg_begin[range], item_end = wg_begin[range + 1];
+  const RangeHeader hdr = ranges[xcd_contiguous_id(blockIdx.x, n_wgs)];
   const int quarter = lane >> 4;
   const uint32_t lane_sub = (uint32_t)(lane & 15) * 16u;  // byte offset of the lane's four tiles in a row
   const __amdgpu_buffer_rsrc_t mr = make_rsrc(Mbuf, m_bytes);
@@ -360,22 +367,34 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(
     voff[u] = idx < total ? ((uint32_t)row * Tp + q * 4) * 4u : 0xfffffff0u;
   }
   u32x4_t piece[kPanelPieces];
-  auto fetch_panel = [&](const WorkItem& w) {
+  auto load_batch = [&](uint32_t byte_off) -> u32x2_t {
+    return __builtin_amdgcn_raw_buffer_load_b64(sr, (int)lane8, (int)byte_off, 0);  // past the end: reads 0
+  };
+
+  // Start of an item, issued as early as the item is known (for the first one: right after the
+  // range header; for the others: after the wave's last slice of the item before): the panel
+  // pieces, then the wave's first slice descriptor and its first two batches, which arrive right
+  // behind the panel, so the first slice starts without another memory round trip.
+  Slice sl;
+  u32x2_t b0 = {0u, 0u}, b1 = {0u, 0u};
+  auto start_item = [&](const WorkItem& w) {
     const uint32_t soff = ((uint32_t)w.p * C * Tp + (uint32_t)w.tau_block * TB) * 4u;
 #pragma unroll
     for (int u = 0; u < kPanelPieces; ++u)
       piece[u] = __builtin_amdgcn_raw_buffer_load_b128(vr, (int)voff[u], (int)soff, 0);
+    const int s = min(w.slice_begin + wave, n_slices - 1);  // clamped: unconditional, in bounds
+    sl = slices[s];
+    b0 = load_batch(sl.batch0 * 512u);
+    b1 = load_batch(sl.batch0 * 512u + 512u);
   };
-  auto load_batch = [&](uint32_t byte_off) -> u32x2_t {
-    return __builtin_amdgcn_raw_buffer_load_b64(sr, (int)lane8, (int)byte_off, 0);  // past the end: reads 0
-  };
-  if (item_begin < item_end) fetch_panel(items[item_begin]);
 
-  for (int item = item_begin; item < item_end; ++item) {
-    const WorkItem it = items[item];
+  WorkItem it = hdr.first;
+  start_item(it);
+  for (int item = hdr.item_begin;; ++item) {
     const int tau0 = it.tau_block * TB;
-    const bool has_next = item + 1 < item_end;
-    if (item != item_begin) __syncthreads();  // every wave is done reading the previous panel
+    const bool has_next = item + 1 < hdr.item_end;
+    const WorkItem it_next = items[has_next ? item + 1 : item];
+    if (item != hdr.item_begin) __syncthreads();  // every wave is done reading the previous panel
 #pragma unroll
     for (int u = 0; u < kPanelPieces; ++u) {
       const int idx = threadIdx.x + u * NT;
@@ -385,51 +404,45 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(
     __syncthreads();
 
     // Waves take slices dynamically, longest first: the first one by wave number, every further
-    // one from a counter in LDS.  The next slice is drawn before the current one is computed, its
-    // first two batches are fetched before the current one's result is stored.
-    int s = it.slice_begin + wave;
-    if (s >= it.slice_end) {
-      if (has_next) fetch_panel(items[item + 1]);
-      continue;
+    // one from a counter in LDS.  The next slice is drawn before the current one is computed.
+    if (it.slice_begin + wave < it.slice_end) {
+      while (true) {
+        int drawn = 0;
+        if (lane == 0) drawn = __hip_atomic_fetch_add(next_slice, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        const int s_next = __builtin_amdgcn_readfirstlane(drawn);
+        const Slice sl_next = slices[min(s_next, n_slices - 1)];  // clamped: unconditional, in bounds
+        const bool more = s_next < it.slice_end;
+        f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        // Two batch registers in turn: batch j of a slice sits in register j % 2.  A register is
+        // refilled right after its batch is consumed, unconditionally, with the batch two ahead -
+        // or, when the slice has no such batch, with batch 0 / 1 of the NEXT slice (parked past
+        // the end of the stream when there is none: reads 0, touches no memory).  So the batches
+        // of a slice are always on their way one or two batches of work before they are needed,
+        // and no wait in the loop ever has more than one younger load in front of it.
+        const uint32_t base = sl.batch0 * 512u, next_base = more ? sl_next.batch0 * 512u : 0xfffff000u;
+        const int batches = (sl.len + kBatchSteps - 1) / kBatchSteps;
+        for (int j = 0, remaining = sl.len; j < batches; j += 2, remaining -= 2 * kBatchSteps) {
+          quarter_batch(panel, lane_sub, b0, remaining, acc);
+          b0 = load_batch(j + 2 < batches ? base + (uint32_t)(j + 2) * 512u : next_base);
+          if (j + 1 < batches) quarter_batch(panel, lane_sub, b1, remaining - kBatchSteps, acc);
+          b1 = load_batch(j + 3 < batches ? base + (uint32_t)(j + 3) * 512u : next_base + 512u);
+        }
+        if (batches == 0) {  // an all-empty slice consumed nothing: fetch the next slice's batches here
+          b0 = load_batch(next_base);
+          b1 = load_batch(next_base + 512u);
+        }
+        // row of this lane's quarter; quarters of padding rows are parked beyond the buffer
+        const int k = quarter == 0 ? sl.k[0] : quarter == 1 ? sl.k[1] : quarter == 2 ? sl.k[2] : sl.k[3];
+        const uint32_t moff =
+            k >= 0 ? (((uint32_t)it.p * K + (uint32_t)k) * Tp + tau0) * 4u + lane_sub : 0xfffffff0u;
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v_t, acc), mr, (int)moff, 0, SWCONV_AUX_M);
+        if (!more) break;
+        sl = sl_next;
+      }
     }
-    Slice sl = slices[s];
-    u32x2_t b0 = load_batch(sl.batch0 * 512u), b1 = load_batch(sl.batch0 * 512u + 512u);
-    while (true) {
-      int drawn = 0;
-      if (lane == 0) drawn = __hip_atomic_fetch_add(next_slice, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      const int s_next = __builtin_amdgcn_readfirstlane(drawn);
-      const Slice sl_next = slices[min(s_next, n_slices - 1)];  // clamped: unconditional, in bounds
-      const bool more = s_next < it.slice_end;
-      f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
-      // Two batch registers in turn: batch j of a slice sits in register j % 2.  A register is
-      // refilled right after its batch is consumed, unconditionally, with the batch two ahead - or,
-      // when the slice has no such batch, with batch 0 / 1 of the NEXT slice (parked past the end
-      // of the stream when there is none: reads 0, touches no memory).  So the batches of a
-      // slice are always on their way one or two batches of work before they are needed, and no
-      // wait in the loop ever has more than one younger load in front of it.
-      const uint32_t base = sl.batch0 * 512u, next_base = more ? sl_next.batch0 * 512u : 0xfffff000u;
-      const int batches = (sl.len + kBatchSteps - 1) / kBatchSteps;
-      for (int j = 0, remaining = sl.len; j < batches; j += 2, remaining -= 2 * kBatchSteps) {
-        quarter_batch(panel, lane_sub, b0, remaining, acc);
-        b0 = load_batch(j + 2 < batches ? base + (uint32_t)(j + 2) * 512u : next_base);
-        if (j + 1 < batches) quarter_batch(panel, lane_sub, b1, remaining - kBatchSteps, acc);
-        b1 = load_batch(j + 3 < batches ? base + (uint32_t)(j + 3) * 512u : next_base + 512u);
-      }
-      if (batches == 0) {  // an all-empty slice consumed nothing: fetch the next slice's batches here
-        b0 = load_batch(next_base);
-        b1 = load_batch(next_base + 512u);
-      }
-      // row of this lane's quarter; quarters of padding rows are parked beyond the buffer
-      const int k = quarter == 0 ? sl.k[0] : quarter == 1 ? sl.k[1] : quarter == 2 ? sl.k[2] : sl.k[3];
-      const uint32_t moff = k >= 0 ? (((uint32_t)it.p * K + (uint32_t)k) * Tp + tau0) * 4u + lane_sub : 0xfffffff0u;
-      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v_t, acc), mr, (int)moff, 0, SWCONV_AUX_M);
-      if (!more) {
-        if (has_next) fetch_panel(items[item + 1]);
-        break;
-      }
-      s = s_next;
-      sl = sl_next;
-    }
+    if (!has_next) break;
+    it = it_next;
+    start_item(it);
   }
 }
 
