@@ -112,7 +112,7 @@ int ensure_workspace(swconv_plan* pl) {
 template <int M>
 int launch_input_transform(const swconv_plan* pl, hipStream_t st, const float* in) {
   dim3 grid(pl->g.Tp / 64, (pl->g.C + 3) / 4);
-  const size_t lds = (size_t)4 * pl->g.slots * pl->g.in_span * sizeof(float);
+  const size_t lds = (size_t)4 * pl->g.in_area * sizeof(float);
   auto kern = input_transform_kernel<M>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -127,7 +127,7 @@ int launch_input_transform(const swconv_plan* pl, hipStream_t st, const float* i
 template <int M>
 int launch_output_transform(const swconv_plan* pl, hipStream_t st, float* out) {
   dim3 grid(pl->g.Tp / 64, (pl->g.K + 3) / 4);
-  const size_t lds = (size_t)4 * pl->g.slots * pl->g.out_span * sizeof(float);
+  const size_t lds = (size_t)4 * pl->g.out_area * sizeof(float);
   auto kern = output_transform_kernel<M>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -172,7 +172,8 @@ int launch_stage(const swconv_plan* pl, hipStream_t st, int stage, const float* 
 // Index tables of the two transform kernels: where each tile and each (tile block, image) part
 // sits in the image and in a wave's LDS staging area.
 void build_transform_tables(swconv_plan* pl) {
-  const Geometry& g = pl->g;
+  Geometry& g = pl->g;
+  g.in_area = g.out_area = 64;
   const int m = pl->m, t = pl->t, nblk = g.Tp / 64;
   TileInfo pad_tile;
   pad_tile.in_org = 0;
@@ -188,6 +189,7 @@ void build_transform_tables(swconv_plan* pl) {
     if (tau0 >= g.T) continue;
     const int last = std::min(tau0 + 63, g.T - 1);
     const int n_first = tau0 / g.tpi, n_last = last / g.tpi;
+    int in_off = 0, out_off = 0;
     for (int n = n_first; n <= n_last; ++n) {
       const int slot = n - n_first, base = n * g.tpi;
       const int t_lo = std::max(tau0, base) - base, t_hi = std::min(last, base + g.tpi - 1) - base;
@@ -203,14 +205,20 @@ void build_transform_tables(swconv_plan* pl) {
       bi.t_lo = t_lo;
       bi.t_hi = t_hi;
       bi.whole = (t_lo % g.tw == 0) && ((t_hi + 1) % g.tw == 0);
+      bi.in_off = in_off;
+      bi.out_off = out_off;
+      in_off += (bi.in_span + 63) / 64 * 64;
+      out_off += (bi.out_span + 63) / 64 * 64;
+      g.in_area = std::max(g.in_area, in_off);
+      g.out_area = std::max(g.out_area, out_off);
       for (int tl = t_lo; tl <= t_hi; ++tl) {
         const int ty = tl / g.tw, tx = tl % g.tw;
         const int y0 = ty * m - g.pad, x0 = tx * m - g.pad;
         TileInfo& ti = pl->tiles[(size_t)base + tl];
-        ti.in_org = slot * g.in_span - y_lo * g.W;
+        ti.in_org = bi.in_off - y_lo * g.W;
         ti.yx0 = (int32_t)(((uint32_t)y0 & 0xffffu) | ((uint32_t)x0 << 16));
         ti.ylim = (int32_t)((uint32_t)y_lo | ((uint32_t)(y_hi - 1) << 16));
-        ti.out_org = slot * g.out_span + (ty * m - oy_lo) * g.Wo + tx * m;
+        ti.out_org = bi.out_off + (ty * m - oy_lo) * g.Wo + tx * m;
       }
     }
   }
@@ -466,15 +474,8 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   }
   g.v_bytes = (uint32_t)((int64_t)P * C * g.Tp * (int64_t)sizeof(float));
   g.m_bytes = (uint32_t)((int64_t)P * K * g.Tp * (int64_t)sizeof(float));
-  // LDS staging bounds of the transform kernels for any run of 64 consecutive tiles
-  const int rows_t = (int)std::min<int64_t>(th, (64 + tw - 2) / tw + 1);
+  // a block of 64 consecutive tiles touches at most this many images
   g.slots = (int)std::min<int64_t>(N, (64 + g.tpi - 2) / g.tpi + 1);
-  g.in_span = (std::min(H, rows_t * m + t - m) * W + 63) / 64 * 64;
-  g.out_span = (std::min(g.Ho, rows_t * m) * g.Wo + 63) / 64 * 64;
-  if ((int64_t)4 * g.slots * std::max(g.in_span, g.out_span) * (int64_t)sizeof(float) > kMaxLdsBytes) {
-    delete pl;
-    return SWCONV_EUNSUPPORTED;
-  }
   pl->n_tau_blocks = (g.T + kTileBlock - 1) / kTileBlock;
   if (H >= 32768 || W >= 32768) {  // 16-bit fields of the tile table
     delete pl;
@@ -487,6 +488,11 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   } catch (const std::bad_alloc&) {
     delete pl;
     return SWCONV_ENOMEM;
+  }
+  // LDS staging areas of the transform kernels (four waves per workgroup)
+  if ((int64_t)4 * std::max(g.in_area, g.out_area) * (int64_t)sizeof(float) > kMaxLdsBytes) {
+    delete pl;
+    return SWCONV_EUNSUPPORTED;
   }
   *out = pl;
   return SWCONV_OK;

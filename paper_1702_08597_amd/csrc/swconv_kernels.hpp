@@ -37,9 +37,10 @@ struct Geometry {
   int T;                    // N*tpi
   int Tp;                   // padded tile count (row pitch of V and M)
   // LDS staging of the transforms: a block of 64 consecutive tiles touches at most `slots` images,
-  // and in each of them a run of whole rows; `in_span` / `out_span` = pitch of one image slot in
-  // floats (the longest run, rounded up to a multiple of 64)
-  int slots, in_span, out_span;
+  // and in each of them a run of whole rows; the runs of a block lie one behind the other in the
+  // wave's staging area, each rounded up to a multiple of 64 floats; `in_area` / `out_area` =
+  // floats of the largest such area over all blocks
+  int slots, in_area, out_area;
   uint32_t v_bytes, m_bytes;  // sizes of the V and M workspaces (both below 4 GiB)
   uint32_t wo_magic;          // ceil(2^32 / Wo): e / Wo == umulhi(e, wo_magic) for every staged element index
   int m_shift;                // log2(m)
@@ -85,6 +86,8 @@ struct BlockImage {
   int32_t out_span;   // output elements of the part (whole rows)
   int32_t t_lo, t_hi; // first / last tile of the block inside the image (image-local tile index)
   int32_t whole;      // 1 when the part consists of whole tile rows (every pixel of the span is owned)
+  int32_t in_off;     // float offset of the part's staged input inside the wave's staging area
+  int32_t out_off;    // float offset of the part's output rows inside the wave's staging area
 };
 
 // One slice = kSliceRows rows of one position's sparse matrix, rows sorted by length.  32 bytes,
@@ -148,13 +151,13 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = blockIdx.y * 4 + wave;
   const int tau0 = blockIdx.x * 64;
-  float* my = stage + wave * g.slots * g.in_span;
+  float* my = stage + wave * g.in_area;
   const BlockImage* bi = blocks + (size_t)blockIdx.x * g.slots;
   const size_t plane = (size_t)g.H * g.W;
   if (c < g.C) {
     // Each image part is read through its own buffer descriptor (base = first staged element,
     // size = the part's bytes): lanes past the end read zeros, so loads and LDS writes need no
-    // lane predicates; slots are pitched to a multiple of 64 floats to take the zero tail.
+    // lane predicates; every part's run is padded to a multiple of 64 floats to take the zero tail.
     constexpr int IG = 4, EL = 4;  // images x loads per lane in flight
     for (int s0 = 0; s0 < g.slots; s0 += IG) {
       __amdgpu_buffer_rsrc_t src[IG];
@@ -167,7 +170,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
         const bool used = s0 + i < g.slots && b.n >= 0;
         span[i] = used ? b.in_span : 0;
         src[i] = make_rsrc(in + ((size_t)max(b.n, 0) * g.C + c) * plane + b.in_elem0, (uint32_t)span[i] * 4u);
-        dst[i] = my + sidx * g.in_span + lane;
+        dst[i] = my + b.in_off + lane;
         max_span = max(max_span, span[i]);
       }
       for (int e0 = 0; e0 < max_span; e0 += 64 * EL) {
@@ -466,7 +469,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
   const int k = blockIdx.y * 4 + wave;
   const int tau0 = blockIdx.x * 64;
   if (tau0 >= g.T) return;  // whole block is padding (uniform for the block)
-  float* my = stage + wave * g.slots * g.out_span;
+  float* my = stage + wave * g.out_area;
   if (k < g.K) {
     const __amdgpu_buffer_rsrc_t mr = make_rsrc(Mbuf, g.m_bytes);
     const uint32_t row0 = ((uint32_t)k * g.Tp + tau0) * 4u;        // wave-uniform byte offset, position 0
@@ -501,7 +504,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
   for (int sidx = 0; sidx < g.slots; ++sidx) {
     const BlockImage b = bi[sidx];
     if (b.n < 0) continue;
-    const float* src = my + sidx * g.out_span;
+    const float* src = my + b.out_off;
     float* dst = out + ((size_t)b.n * g.K + k) * plane + b.out_elem0;
     // stores past the part's end are dropped by the descriptor: no lane predicate
     const __amdgpu_buffer_rsrc_t orr = make_rsrc(dst, (uint32_t)b.out_span * 4u);
