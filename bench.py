@@ -24,8 +24,8 @@ STAGES = ("input_transform_kernel", "spmm_kernel", "output_transform_kernel")
 # HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain
 # copy of known size (profiles/pmc_traffic_alexnet_conv3_n32_f4.md); known for the default workload only.
 MEASURED_TRAFFIC = {
-    ("alexnet_conv3_n32_f4", 0.10): {"input_transform_kernel": 24.52e6, "spmm_kernel": 54.66e6,
-                                     "output_transform_kernel": 36.69e6},
+    ("alexnet_conv3_n32_f4", 0.10): {"input_transform_kernel": 24.51e6, "spmm_kernel": 52.06e6,
+                                     "output_transform_kernel": 37.72e6},
 }
 
 
@@ -123,8 +123,8 @@ def main():
     }
 
     if not args.dense:
-        # per-kernel durations: HIP events on the launch stream around each kernel, over the same
-        # number of steps as the timed region
+        # per-kernel durations: a pair of HIP events attached to every kernel launch on the launch
+        # stream (the kernel's own start and end time stamps), over as many steps as the timed region
         stage_ms = sw.swconv_profile_forward(plan, sp, xp, op, args.steps)
         models = stage_models(cfg, nnz)
         stages = []

@@ -114,9 +114,10 @@ int swconv_set_weights_dense(swconv_plan* plan, const float* wf);
 int swconv_forward_dense(swconv_plan* plan, void* hip_stream, const float* in_dev, float* out_dev);
 
 /*
- * Measurement helper: run `iters` sparse forward passes on `hip_stream` with HIP events
- * recorded on that stream around each of the three kernels, synchronise, and return the
- * mean duration of each step in milliseconds.
+ * Measurement helper: run `iters` sparse forward passes on `hip_stream`, every kernel launched
+ * with a pair of HIP events that take the kernel's own start and end time stamps on that stream
+ * (no extra packets between the kernels), synchronise, and return the mean duration of each
+ * step in milliseconds.
  *   stage_ms  HOST, 3 floats: input transform, sparse product, output transform.
  * Blocks the host.  Errors as for swconv_forward; EINVAL for iters < 1.
  */

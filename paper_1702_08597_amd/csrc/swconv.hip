@@ -2,6 +2,7 @@
 // Implements the C ABI declared in include/swconv.h.
 #include "../../include/swconv.h"
 
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -109,8 +110,25 @@ int ensure_workspace(swconv_plan* pl) {
   return SWCONV_OK;
 }
 
+// Where a kernel goes: the stream and, for swconv_profile_forward, a pair of events that take the
+// kernel's own start and end time stamps (no extra packets on the stream).
+struct LaunchTarget {
+  hipStream_t stream;
+  hipEvent_t start, stop;
+};
+
+template <typename... Params, typename... Args>
+int launch_kernel(void (*kern)(Params...), dim3 grid, dim3 block, size_t lds, const LaunchTarget& to, Args... args) {
+  if (to.start || to.stop)
+    hipExtLaunchKernelGGL(kern, grid, block, (uint32_t)lds, to.stream, to.start, to.stop, 0u, Params(args)...);
+  else
+    hipLaunchKernelGGL(kern, grid, block, lds, to.stream, Params(args)...);
+  HIP_TRY(hipGetLastError());
+  return SWCONV_OK;
+}
+
 template <int M>
-int launch_input_transform(const swconv_plan* pl, hipStream_t st, const float* in) {
+int launch_input_transform(const swconv_plan* pl, const LaunchTarget& to, const float* in) {
   dim3 grid(pl->g.Tp / 64, (pl->g.C + 3) / 4);
   const size_t lds = (size_t)4 * pl->g.in_area * sizeof(float);
   auto kern = input_transform_kernel<M>;
@@ -119,13 +137,11 @@ int launch_input_transform(const swconv_plan* pl, hipStream_t st, const float* i
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, in, pl->dV, pl->d_tiles, pl->d_blocks, pl->g);
-  HIP_TRY(hipGetLastError());
-  return SWCONV_OK;
+  return launch_kernel(kern, grid, dim3(256), lds, to, in, pl->dV, pl->d_tiles, pl->d_blocks, pl->g);
 }
 
 template <int M>
-int launch_output_transform(const swconv_plan* pl, hipStream_t st, float* out) {
+int launch_output_transform(const swconv_plan* pl, const LaunchTarget& to, float* out) {
   dim3 grid(pl->g.Tp / 64, (pl->g.K + 3) / 4);
   const size_t lds = (size_t)4 * pl->g.out_area * sizeof(float);
   auto kern = output_transform_kernel<M>;
@@ -134,13 +150,11 @@ int launch_output_transform(const swconv_plan* pl, hipStream_t st, float* out) {
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, pl->dM, out, pl->d_tiles, pl->d_blocks, pl->g);
-  HIP_TRY(hipGetLastError());
-  return SWCONV_OK;
+  return launch_kernel(kern, grid, dim3(256), lds, to, pl->dM, out, pl->d_tiles, pl->d_blocks, pl->g);
 }
 
 template <int NW>
-int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
+int launch_spmm_t(const swconv_plan* pl, const LaunchTarget& to) {
   if (pl->n_wgs_used == 0) return SWCONV_OK;
   const size_t lds = (size_t)pl->g.C * kTileBlock * sizeof(float) + kSpmmLdsExtra;
   auto kern = spmm_kernel<NW>;
@@ -149,23 +163,21 @@ int launch_spmm_t(const swconv_plan* pl, hipStream_t st) {
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(pl->n_wgs_used), dim3(NW * 64), lds, st, pl->dV, pl->dM, pl->d_stream,
-                     (uint32_t)(pl->stream.size() * sizeof(uint32_t)), pl->d_slices, (int)pl->slices.size(),
-                     pl->d_items, pl->d_ranges, pl->n_wgs_used, pl->g.C, pl->g.K, pl->g.Tp, pl->g.m_bytes,
-                     pl->g.v_bytes);
-  HIP_TRY(hipGetLastError());
-  return SWCONV_OK;
+  return launch_kernel(kern, dim3(pl->n_wgs_used), dim3(NW * 64), lds, to, pl->dV, pl->dM, pl->d_stream,
+                       (uint32_t)(pl->stream.size() * sizeof(uint32_t)), pl->d_slices, (int)pl->slices.size(),
+                       pl->d_items, pl->d_ranges, pl->n_wgs_used, pl->g.C, pl->g.K, pl->g.Tp, pl->g.m_bytes,
+                       pl->g.v_bytes);
 }
 
-int launch_spmm(const swconv_plan* pl, hipStream_t st) {
-  return pl->waves == 16 ? launch_spmm_t<16>(pl, st) : launch_spmm_t<8>(pl, st);
+int launch_spmm(const swconv_plan* pl, const LaunchTarget& to) {
+  return pl->waves == 16 ? launch_spmm_t<16>(pl, to) : launch_spmm_t<8>(pl, to);
 }
 
-int launch_stage(const swconv_plan* pl, hipStream_t st, int stage, const float* in, float* out) {
+int launch_stage(const swconv_plan* pl, const LaunchTarget& to, int stage, const float* in, float* out) {
   switch (stage) {
-    case 0: return pl->m == 2 ? launch_input_transform<2>(pl, st, in) : launch_input_transform<4>(pl, st, in);
-    case 1: return launch_spmm(pl, st);
-    default: return pl->m == 2 ? launch_output_transform<2>(pl, st, out) : launch_output_transform<4>(pl, st, out);
+    case 0: return pl->m == 2 ? launch_input_transform<2>(pl, to, in) : launch_input_transform<4>(pl, to, in);
+    case 1: return launch_spmm(pl, to);
+    default: return pl->m == 2 ? launch_output_transform<2>(pl, to, out) : launch_output_transform<4>(pl, to, out);
   }
 }
 
@@ -536,9 +548,9 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
 int swconv_forward(swconv_plan* pl, void* hip_stream, const float* in_dev, float* out_dev) {
   if (!pl || !in_dev || !out_dev) return SWCONV_EINVAL;
   if (!pl->sparse_on_device) return SWCONV_ESTATE;
-  hipStream_t st = (hipStream_t)hip_stream;
+  const LaunchTarget to{(hipStream_t)hip_stream, nullptr, nullptr};
   for (int stage = 0; stage < 3; ++stage) {
-    int rc = launch_stage(pl, st, stage, in_dev, out_dev);
+    int rc = launch_stage(pl, to, stage, in_dev, out_dev);
     if (rc) return rc;
   }
   pl->ran_forward = true;
@@ -550,25 +562,24 @@ int swconv_profile_forward(swconv_plan* pl, void* hip_stream, const float* in_de
   if (!pl || !in_dev || !out_dev || !stage_ms || iters < 1) return SWCONV_EINVAL;
   if (!pl->sparse_on_device) return SWCONV_ESTATE;
   hipStream_t st = (hipStream_t)hip_stream;
-  std::vector<hipEvent_t> ev((size_t)iters * 4, nullptr);
+  // one (start, stop) pair per kernel launch; the events take the kernel's own time stamps
+  std::vector<hipEvent_t> ev((size_t)iters * 6, nullptr);
   int rc = SWCONV_OK;
   for (auto& e : ev)
     if (hipEventCreate(&e) != hipSuccess) rc = SWCONV_EHIP;
-  for (int it = 0; it < iters && !rc; ++it) {
-    hipEvent_t* e = &ev[(size_t)it * 4];
-    if (hipEventRecord(e[0], st) != hipSuccess) rc = SWCONV_EHIP;
+  for (int it = 0; it < iters && !rc; ++it)
     for (int stage = 0; stage < 3 && !rc; ++stage) {
-      rc = launch_stage(pl, st, stage, in_dev, out_dev);
-      if (!rc && hipEventRecord(e[stage + 1], st) != hipSuccess) rc = SWCONV_EHIP;
+      hipEvent_t* e = &ev[((size_t)it * 3 + stage) * 2];
+      rc = launch_stage(pl, LaunchTarget{st, e[0], e[1]}, stage, in_dev, out_dev);
     }
-  }
   if (hipStreamSynchronize(st) != hipSuccess) rc = rc ? rc : SWCONV_EHIP;
   if (!rc) {
     double sum[3] = {0, 0, 0};
     for (int it = 0; it < iters && !rc; ++it)
       for (int stage = 0; stage < 3; ++stage) {
+        hipEvent_t* e = &ev[((size_t)it * 3 + stage) * 2];
         float ms = 0;
-        if (hipEventElapsedTime(&ms, ev[(size_t)it * 4 + stage], ev[(size_t)it * 4 + stage + 1]) != hipSuccess) {
+        if (hipEventElapsedTime(&ms, e[0], e[1]) != hipSuccess) {
           rc = SWCONV_EHIP;
           break;
         }
@@ -695,7 +706,8 @@ int swconv_forward_dense(swconv_plan* pl, void* hip_stream, const float* in_dev,
   if (!pl || !in_dev || !out_dev) return SWCONV_EINVAL;
   if (!pl->dense_on_device) return SWCONV_ESTATE;
   hipStream_t st = (hipStream_t)hip_stream;
-  int rc = launch_stage(pl, st, 0, in_dev, out_dev);
+  const LaunchTarget to{st, nullptr, nullptr};
+  int rc = launch_stage(pl, to, 0, in_dev, out_dev);
   if (rc) return rc;
   {
     const Geometry& g = pl->g;
@@ -704,7 +716,7 @@ int swconv_forward_dense(swconv_plan* pl, void* hip_stream, const float* in_dev,
                        pl->Kq, g.C, g.Tp);
     HIP_TRY(hipGetLastError());
   }
-  rc = launch_stage(pl, st, 2, in_dev, out_dev);
+  rc = launch_stage(pl, to, 2, in_dev, out_dev);
   if (rc) return rc;
   pl->ran_forward = true;
   return SWCONV_OK;
