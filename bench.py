@@ -6,7 +6,7 @@ output transform) over one batch of seeded synthetic input that is already resid
 Metric: effective TFLOP/s = FLOPs a dense direct convolution would execute / time (the paper's
 Fig. 2 definition).  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--density D]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--density D] [--rotate R]
 """
 import argparse
 import json
@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--dense", action="store_true", help="time the 0%%-sparsity MFMA comparison path instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rotate", type=int, default=1, metavar="R",
+                    help="cold-cache regime: step i runs on the i %% R-th of R independent sets of plan, workspaces, "
+                         "input and output (choose R so that the sets exceed the 256 MB Infinity Cache)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run 20 plain device copies of this many MiB (a kernel of known "
                          "HBM traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc)")
@@ -91,19 +94,27 @@ def main():
     if args.dense:
         wf = synth.dense_weights(cfg["P"], cfg["K"], cfg["C"], cfg["seed"] + 2000)
         sw.swconv_set_weights_dense(plan, wf)
-        step = lambda: sw.swconv_forward_dense(plan, sp, xp, op)
+        step = lambda i: sw.swconv_forward_dense(plan, sp, xp, op)
     else:
         t0 = time.perf_counter()
         sw.swconv_set_weights(plan, rp, ci, va)
         set_weights_ms = (time.perf_counter() - t0) * 1e3
-        step = lambda: sw.swconv_forward(plan, sp, xp, op)
+        sets = [(plan, xp, op)]
+        keep = []
+        for _ in range(1, max(1, args.rotate)):
+            p2 = sw.swconv_plan_create(cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"], cfg["m"], cfg["r"], cfg["pad"])
+            sw.swconv_set_weights(p2, rp, ci, va)
+            x2, o2 = xd.clone(), torch.empty_like(out)
+            keep.append((x2, o2))
+            sets.append((p2, x2.data_ptr(), o2.data_ptr()))
+        step = lambda i: sw.swconv_forward(sets[i % len(sets)][0], sp, sets[i % len(sets)][1], sets[i % len(sets)][2])
 
-    for _ in range(args.warmup):
-        step()
+    for i in range(args.warmup):
+        step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    for i in range(args.steps):
+        step(i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
@@ -117,7 +128,9 @@ def main():
         "config": {"workload": name, "N": cfg["N"], "C": cfg["C"], "H": cfg["H"], "W": cfg["W"], "K": cfg["K"],
                    "winograd": "F(%dx%d,3x3)" % (cfg["m"], cfg["m"]), "pad": cfg["pad"],
                    "density": (nnz / float(cfg["P"] * cfg["K"] * cfg["C"])), "nnz": nnz,
-                   "path": "dense-mfma-comparison" if args.dense else "sparse"},
+                   "path": "dense-mfma-comparison" if args.dense else "sparse",
+                   "cache_regime": "warm (one buffer set)" if args.rotate <= 1 or args.dense
+                                   else "cold (%d buffer sets in rotation)" % args.rotate},
         "paper_context": {"value": 31.7, "unit": "effective TFLOP/s fp32", "hardware": "2x Xeon Platinum 8180 (56 cores)",
                           "note": "paper's peak on pruned AlexNet 3x3 layers, batch 56; another machine and model"},
     }
@@ -175,6 +188,9 @@ def main():
                                             % (n_img, len(times)),
                                   "seconds": round(t_med, 4)}
 
+    if not args.dense:
+        for p2, _, _ in sets[1:]:
+            sw.swconv_plan_destroy(p2)
     sw.swconv_plan_destroy(plan)
     print(json.dumps(result))
 

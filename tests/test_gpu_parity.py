@@ -160,6 +160,24 @@ def test_row_permutation_is_bit_exact_and_runs_are_deterministic():
         L.close()
 
 
+def test_full_rows_stored_zeros_and_lone_rows_through_the_sparse_path():
+    """Stream edge cases of the packed layout: every row full (many batches per slice), explicit
+    stored zeros, and positions where one row is full and all others are empty (a slice whose
+    other rows are pure padding; all-empty slices next to it)."""
+    m, N, C, H, W, K = 4, 5, 70, 9, 9, 9
+    P = 36
+    rng = np.random.default_rng(77)
+    x = synth.activations(N, C, H, W, 78)
+    dense = rng.normal(0, 0.05, size=(P, K, C)).astype(np.float32)
+    mask = np.ones((P, K, C), dtype=bool)
+    dense[:, :, ::7] = 0.0          # stored zeros: kept in the pattern
+    mask[1::2] = False              # odd positions: only row 3 is populated
+    mask[1::2, 3, :] = True
+    rp, ci, va = synth.dense_to_csr(mask, dense)
+    assert (va == 0).any()
+    check_against_oracle(N, C, H, W, K, m, 1, x, rp, ci, va)
+
+
 FULL = ["alexnet_conv3_n1_f2", "alexnet_conv3_n32_f4", "alexnet_conv4_n64_f4", "alexnet_conv5_n64_f4",
         "conv4_skewed_n64_f4"]
 
