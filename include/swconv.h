@@ -65,7 +65,7 @@ const char* swconv_status_string(int status);
  * first swconv_set_weights / swconv_set_weights_dense on the then-current HIP device.
  * Errors: EINVAL for non-positive sizes, pad < 0, Ho or Wo < 1 or index ranges beyond int32;
  * EUNSUPPORTED for an unsupported (m,r) or a shape whose panels do not fit the kernels' LDS
- * budget (C > 639).  On success *out owns the plan; release with swconv_plan_destroy.
+ * budget (C > 638).  On success *out owns the plan; release with swconv_plan_destroy.
  */
 int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int m, int r, int pad);
 
@@ -144,7 +144,8 @@ int swconv_debug_export_weights(swconv_plan* plan, int32_t* rowptr, int32_t* col
 
 /*
  * Verifies the static schedule of the sparse product on the host: every (position, tile block,
- * slice) unit is assigned to exactly one persistent workgroup and no launched workgroup is idle.
+ * slice) unit is assigned to exactly one persistent workgroup, no launched workgroup is idle and
+ * no work item has more slices than the kernel stages descriptors for.
  * Returns SWCONV_OK, or SWCONV_EINVAL when the schedule is not a partition; ESTATE when no sparse
  * weights were set.  Needs no GPU.
  */

@@ -20,7 +20,7 @@ using namespace swconv;
 namespace {
 
 constexpr int kMaxLdsBytes = 160 * 1024;
-constexpr int kSpmmLdsExtra = 64;    // the sparse product's slice counter sits behind the panel
+constexpr int kSpmmLdsExtra = 64;    // the sparse product's slice counter sits behind the panel, then the slice descriptors
 
 int env_int(const char* name, int dflt) {
   const char* s = std::getenv(name);
@@ -57,6 +57,7 @@ struct swconv_plan {
   Geometry g{};
   int m = 0, r = 0, t = 0, P = 0;
   int waves = 8; // waves per workgroup in the sparse product
+  int item_cap = kMaxItemSlices;  // most slices a work item may have (their descriptors are staged in LDS)
   int Kp = 0;    // K rounded up to a multiple of the slice height
   int Kq = 0;    // K rounded up to the dense GEMM's row tile
   int n_tau_blocks = 0;
@@ -156,7 +157,7 @@ int launch_output_transform(const swconv_plan* pl, const LaunchTarget& to, float
 template <int NW>
 int launch_spmm_t(const swconv_plan* pl, const LaunchTarget& to) {
   if (pl->n_wgs_used == 0) return SWCONV_OK;
-  const size_t lds = (size_t)pl->g.C * kTileBlock * sizeof(float) + kSpmmLdsExtra;
+  const size_t lds = (size_t)pl->g.C * kTileBlock * sizeof(float) + kSpmmLdsExtra + (size_t)pl->item_cap * sizeof(Slice);
   auto kern = spmm_kernel<NW>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -170,6 +171,7 @@ int launch_spmm_t(const swconv_plan* pl, const LaunchTarget& to) {
 }
 
 int launch_spmm(const swconv_plan* pl, const LaunchTarget& to) {
+  if (pl->waves == 12) return launch_spmm_t<12>(pl, to);
   return pl->waves == 16 ? launch_spmm_t<16>(pl, to) : launch_spmm_t<8>(pl, to);
 }
 
@@ -296,14 +298,14 @@ void build_schedule(swconv_plan* pl) {
           open_wg = true;
           acc += panel_cost;
           const int s0 = s;
-          while (s < s_end) {
+          while (s < s_end && s - s0 < pl->item_cap) {
             const int64_t c = pl->slices[s].len + slice_ovh;
             if (s > s0 && acc + c > budget) break;
             acc += c;
             ++s;
           }
           if (items) items->push_back(WorkItem{p, tb, s0, s});
-          if (s < s_end) close_wg();
+          if (s < s_end && s - s0 < pl->item_cap) close_wg();  // the budget, not the item cap, ended the item
         }
       }
     close_wg();
@@ -455,23 +457,29 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
 
   swconv_plan* pl = new (std::nothrow) swconv_plan();
   if (!pl) return SWCONV_ENOMEM;
-  // the sparse product stages a C x 64 panel (256 bytes per channel) plus its slice counter in LDS
-  const int64_t panel_budget = kMaxLdsBytes - kSpmmLdsExtra;
+  // the sparse product stages a C x 64 panel (256 bytes per channel), its slice counter and the
+  // descriptors of at least kMinItemSlices slices in LDS
   const int64_t panel_bytes = (int64_t)C * kTileBlock * (int64_t)sizeof(float);
-  if (panel_bytes > panel_budget) {
+  const int64_t desc_room = (kMaxLdsBytes - kSpmmLdsExtra - panel_bytes) / (int64_t)sizeof(Slice);
+  if (desc_room < kMinItemSlices) {
     delete pl;
     return SWCONV_EUNSUPPORTED;
   }
+  pl->item_cap = (int)std::min<int64_t>(kMaxItemSlices, desc_room);
   pl->m = m;
   pl->r = r;
   pl->t = t;
   pl->P = P;
-  // two workgroups of 8 waves per CU while two panels fit LDS, else one of 16
-  const int dflt_waves = panel_bytes * 2 + 2 * kSpmmLdsExtra > kMaxLdsBytes ? 16 : 8;
-  pl->waves = env_int("SWCONV_SPMM_WAVES", dflt_waves) == 16 ? 16 : 8;
+  // two workgroups of 12 waves per CU while two panels fit LDS (six waves per SIMD hide the LDS and
+  // draw latencies better than four), else one of 16
+  const int64_t wg_lds = panel_bytes + kSpmmLdsExtra + (int64_t)std::min<int64_t>(pl->item_cap, (K + kSliceRows - 1) / kSliceRows) * (int64_t)sizeof(Slice);
+  const int dflt_waves = wg_lds * 2 > kMaxLdsBytes ? 16 : 12;
+  pl->waves = env_int("SWCONV_SPMM_WAVES", dflt_waves);
+  if (pl->waves != 8 && pl->waves != 12 && pl->waves != 16) pl->waves = dflt_waves;
   // a thread stages at most kPanelPieces 16-byte pieces of a panel
   if (panel_bytes > (int64_t)kPanelPieces * pl->waves * 64 * 16) pl->waves = 16;
   pl->Kp = (K + kSliceRows - 1) / kSliceRows * kSliceRows;
+  pl->item_cap = std::min(pl->item_cap, pl->Kp / kSliceRows);
   Geometry& g = pl->g;
   g.N = N; g.C = C; g.H = H; g.W = W; g.K = K; g.pad = pad;
   g.Ho = (int)Ho; g.Wo = (int)Wo; g.th = (int)th; g.tw = (int)tw; g.tpi = (int)(th * tw);
@@ -531,7 +539,7 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
       cus = prop.multiProcessorCount;
     else
       (void)hipGetLastError();
-    const size_t panel_bytes = (size_t)pl->g.C * kTileBlock * sizeof(float) + kSpmmLdsExtra;
+    const size_t panel_bytes = (size_t)pl->g.C * kTileBlock * sizeof(float) + kSpmmLdsExtra + (size_t)pl->item_cap * sizeof(Slice);
     const int per_cu = std::max<int>(1, std::min<int>(32 / pl->waves, (int)(kMaxLdsBytes / panel_bytes)));
     pl->n_wgs = std::max(1, env_int("SWCONV_SPMM_WGS", cus * per_cu));
   }
@@ -648,6 +656,7 @@ int swconv_debug_check_schedule(const swconv_plan* pl) {
   for (const WorkItem& w : pl->items) {
     if (w.p < 0 || w.p >= pl->P || w.tau_block < 0 || w.tau_block >= ntb) return SWCONV_EINVAL;
     if (w.slice_begin < w.p * spp || w.slice_end > (w.p + 1) * spp || w.slice_begin >= w.slice_end) return SWCONV_EINVAL;
+    if (w.slice_end - w.slice_begin > pl->item_cap) return SWCONV_EINVAL;  // descriptors must fit their LDS area
     for (int sidx = w.slice_begin; sidx < w.slice_end; ++sidx) {
       uint8_t& f = seen[((size_t)w.p * ntb + w.tau_block) * spp + (sidx - w.p * spp)];
       if (f) return SWCONV_EINVAL;

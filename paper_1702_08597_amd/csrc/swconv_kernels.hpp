@@ -121,6 +121,9 @@ constexpr int kTileBlock = 64;   // tiles per panel row: 16 lanes of a quarter x
 constexpr int kBatchSteps = 16;  // steps per 512-byte stream batch (one per lane of a quarter)
 constexpr int kStepGroup = 4;    // steps issued together; a slice's length is a multiple of it
 constexpr int kPanelPieces = 10; // 16-byte panel pieces a thread holds in registers
+constexpr int kMaxItemSlices = 256;  // slices per work item: their descriptors are staged in LDS, two 16-byte
+                                     // pieces each, one piece per thread of the smallest workgroup (512 threads)
+constexpr int kMinItemSlices = 8;    // the least the LDS left over by a large panel must hold
 constexpr int kXcds = 8;
 
 // Workgroup ids are dealt round-robin to the 8 XCDs; remap them so that each XCD gets one
@@ -277,12 +280,18 @@ __device__ __forceinline__ uint32_t quarter_bcast(uint32_t x) {
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4v_t __attribute__((ext_vector_type(4)));
 
+// The four accumulators of a lane (its four tiles); separate scalars, so that the inline-asm FMAs
+// update them in place.
+struct Acc4 {
+  float a0, a1, a2, a3;
+};
+
 // acc += w * x with w taken from lane I of the lane's quarter.  The broadcast rides on the FMAs
 // themselves (DPP operand); the compiler would spend a separate move on it.  `bw` is only ever
 // written by a memory load, and FIRST puts two wait states in front, so the rule "two wait states
 // between a vector-ALU write of a register and a DPP read of it" holds whatever precedes the group.
 template <int I, bool FIRST>
-__device__ __forceinline__ void quarter_fma(f32x4_t& acc, uint32_t bw, const f32x4_t& x) {
+__device__ __forceinline__ void quarter_fma(Acc4& acc, uint32_t bw, const f32x4_t& x) {
 #define SWCONV_QFMA(N)                                                                         \
   "v_fmac_f32_dpp %0, %4, %5 row_newbcast:" #N " row_mask:0xf bank_mask:0xf\n"                 \
   "v_fmac_f32_dpp %1, %4, %6 row_newbcast:" #N " row_mask:0xf bank_mask:0xf\n"                 \
@@ -292,11 +301,11 @@ __device__ __forceinline__ void quarter_fma(f32x4_t& acc, uint32_t bw, const f32
   if constexpr (I == N) {                                                                      \
     if constexpr (FIRST)                                                                       \
       asm("s_nop 1\n" SWCONV_QFMA(N)                                                           \
-          : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])                             \
+          : "+v"(acc.a0), "+v"(acc.a1), "+v"(acc.a2), "+v"(acc.a3)                             \
           : "v"(bw), "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]));                              \
     else                                                                                       \
       asm(SWCONV_QFMA(N)                                                                       \
-          : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])                             \
+          : "+v"(acc.a0), "+v"(acc.a1), "+v"(acc.a2), "+v"(acc.a3)                             \
           : "v"(bw), "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]));                              \
   }
   SWCONV_QFMA_CASE(0) SWCONV_QFMA_CASE(1) SWCONV_QFMA_CASE(2) SWCONV_QFMA_CASE(3)
@@ -311,7 +320,7 @@ __device__ __forceinline__ void quarter_fma(f32x4_t& acc, uint32_t bw, const f32
 // are issued back to back, the FMAs follow as the data arrives.
 template <int G>
 __device__ __forceinline__ void quarter_group(const float* panel, uint32_t lane_sub, uint32_t boff, uint32_t bw,
-                                              f32x4_t& acc) {
+                                              Acc4& acc) {
   constexpr int I0 = G * kStepGroup;
   static_assert(kStepGroup == 4, "four steps per group");
   const char* base = reinterpret_cast<const char*>(panel);
@@ -327,7 +336,7 @@ __device__ __forceinline__ void quarter_group(const float* panel, uint32_t lane_
 
 // The first `steps` (a positive multiple of kStepGroup, wave-uniform) steps of one batch.
 __device__ __forceinline__ void quarter_batch(const float* panel, uint32_t lane_sub, const u32x2_t& b, int steps,
-                                              f32x4_t& acc) {
+                                              Acc4& acc) {
   quarter_group<0>(panel, lane_sub, b.x, b.y, acc);
   if (steps > 1 * kStepGroup) quarter_group<1>(panel, lane_sub, b.x, b.y, acc);
   if (steps > 2 * kStepGroup) quarter_group<2>(panel, lane_sub, b.x, b.y, acc);
@@ -335,14 +344,18 @@ __device__ __forceinline__ void quarter_batch(const float* panel, uint32_t lane_
 }
 
 template <int NWAVES>
-__global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(
+__global__ __launch_bounds__(NWAVES * 64, NWAVES == 12 ? 6 : 4) void spmm_kernel(
     const float* __restrict__ V, float* __restrict__ Mbuf, const uint32_t* __restrict__ stream, uint32_t stream_bytes,
     const Slice* __restrict__ slices, int n_slices, const WorkItem* __restrict__ items,
     const RangeHeader* __restrict__ ranges, int n_wgs, int C, int K, int Tp, uint32_t m_bytes, uint32_t v_bytes) {
   constexpr int NT = NWAVES * 64;
   constexpr int TB = kTileBlock;
-  extern __shared__ float panel[];  // [C][64], at LDS offset 0 of the workgroup, then the slice counter
+  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  // LDS: the panel [C][64] at offset 0 of the workgroup, the slice counter (64 bytes), then the
+  // descriptors of the item's slices
+  extern __shared__ float panel[];
   int* next_slice = reinterpret_cast<int*>(panel + (size_t)C * TB);
+  u32x4_t* desc = reinterpret_cast<u32x4_t*>(panel + (size_t)C * TB + 16);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const RangeHeader hdr = ranges[xcd_contiguous_id(blockIdx.x, n_wgs)];
@@ -350,6 +363,7 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(
   const uint32_t lane_sub = (uint32_t)(lane & 15) * 16u;  // byte offset of the lane's four tiles in a row
   const __amdgpu_buffer_rsrc_t mr = make_rsrc(Mbuf, m_bytes);
   const __amdgpu_buffer_rsrc_t sr = make_rsrc(stream, stream_bytes);
+  const __amdgpu_buffer_rsrc_t dr = make_rsrc(slices, (uint32_t)n_slices * (uint32_t)sizeof(Slice));
   const uint32_t lane8 = (uint32_t)lane * 8u;
 
   // Panel staging: thread i moves the 16-byte pieces i, i + NT, ... of a panel; their offsets
@@ -357,8 +371,10 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(
   // travels through registers.  Vector-memory results come back in issue order and the stream
   // batches use the same path, so a wave asks for the next panel only after its last slice of the
   // item: a wait on a batch never has a panel load in front of it.  (Surplus pieces are parked
-  // past the end of the buffer and read 0 without touching memory.)
-  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  // past the end of the buffer and read 0 without touching memory.)  The descriptors of the item's
+  // slices (32 bytes each, at most kMaxItemSlices) are staged the same way, one 16-byte piece per
+  // thread: drawing a slice then costs an LDS atomic and an LDS read, and no scalar-memory load -
+  // which shares its counter with the LDS reads of the inner loop - is in flight while it runs.
   constexpr int v4_per_row = TB / 4;
   const int total = C * v4_per_row;
   const __amdgpu_buffer_rsrc_t vr = make_rsrc(V, v_bytes);
@@ -369,78 +385,103 @@ __global__ __launch_bounds__(NWAVES * 64) void spmm_kernel(
     const int row = idx / v4_per_row, q = idx % v4_per_row;
     voff[u] = idx < total ? ((uint32_t)row * Tp + q * 4) * 4u : 0xfffffff0u;
   }
-  u32x4_t piece[kPanelPieces];
+  u32x4_t piece[kPanelPieces], desc_piece;
   auto load_batch = [&](uint32_t byte_off) -> u32x2_t {
     return __builtin_amdgcn_raw_buffer_load_b64(sr, (int)lane8, (int)byte_off, 0);  // past the end: reads 0
   };
 
+  // A slice as the loop holds it: stream position and length in scalar registers, the output
+  // channel of the lane's quarter in a vector register (-1 = padding row).
+  struct Cur {
+    uint32_t base;  // byte offset of the slice's first batch
+    int len;        // steps
+    int k;          // per lane
+  };
+  auto quarter_k = [&](int k0, int k1, int k2, int k3) {
+    return quarter == 0 ? k0 : quarter == 1 ? k1 : quarter == 2 ? k2 : k3;
+  };
+
   // Start of an item, issued as early as the item is known (for the first one: right after the
   // range header; for the others: after the wave's last slice of the item before): the panel
-  // pieces, then the wave's first slice descriptor and its first two batches, which arrive right
-  // behind the panel, so the first slice starts without another memory round trip.
-  Slice sl;
+  // pieces and the descriptor piece, then the wave's first slice descriptor and its first two
+  // batches, which arrive right behind the panel, so the first slice starts without another
+  // memory round trip.
+  Cur cur;
   u32x2_t b0 = {0u, 0u}, b1 = {0u, 0u};
   auto start_item = [&](const WorkItem& w) {
     const uint32_t soff = ((uint32_t)w.p * C * Tp + (uint32_t)w.tau_block * TB) * 4u;
 #pragma unroll
     for (int u = 0; u < kPanelPieces; ++u)
       piece[u] = __builtin_amdgcn_raw_buffer_load_b128(vr, (int)voff[u], (int)soff, 0);
-    const int s = min(w.slice_begin + wave, n_slices - 1);  // clamped: unconditional, in bounds
-    sl = slices[s];
-    b0 = load_batch(sl.batch0 * 512u);
-    b1 = load_batch(sl.batch0 * 512u + 512u);
+    const int n_desc_pieces = 2 * (w.slice_end - w.slice_begin);
+    desc_piece = __builtin_amdgcn_raw_buffer_load_b128(
+        dr, (int)((int)threadIdx.x < n_desc_pieces ? threadIdx.x * 16u : 0xfffffff0u),
+        (int)((uint32_t)w.slice_begin * (uint32_t)sizeof(Slice)), 0);
+    const Slice sl = slices[min(w.slice_begin + wave, n_slices - 1)];  // clamped: unconditional, in bounds
+    cur.base = sl.batch0 * 512u;
+    cur.len = sl.len;
+    cur.k = quarter_k(sl.k[0], sl.k[1], sl.k[2], sl.k[3]);
+    b0 = load_batch(cur.base);
+    b1 = load_batch(cur.base + 512u);
   };
 
   WorkItem it = hdr.first;
   start_item(it);
   for (int item = hdr.item_begin;; ++item) {
     const int tau0 = it.tau_block * TB;
+    const int n_item_slices = it.slice_end - it.slice_begin;
     const bool has_next = item + 1 < hdr.item_end;
     const WorkItem it_next = items[has_next ? item + 1 : item];
-    if (item != hdr.item_begin) __syncthreads();  // every wave is done reading the previous panel
+    if (item != hdr.item_begin) __syncthreads();  // every wave is done with the previous panel and descriptors
 #pragma unroll
     for (int u = 0; u < kPanelPieces; ++u) {
       const int idx = threadIdx.x + u * NT;
       if (idx < total) *reinterpret_cast<u32x4_t*>(panel + idx * 4) = piece[u];
     }
-    if (threadIdx.x == 0) *next_slice = it.slice_begin + NWAVES;
+    if ((int)threadIdx.x < 2 * n_item_slices) desc[threadIdx.x] = desc_piece;
+    if (threadIdx.x == 0) *next_slice = NWAVES;  // item-local index of the first slice to be drawn
     __syncthreads();
 
     // Waves take slices dynamically, longest first: the first one by wave number, every further
     // one from a counter in LDS.  The next slice is drawn before the current one is computed.
-    if (it.slice_begin + wave < it.slice_end) {
+    if (wave < n_item_slices) {
       while (true) {
         int drawn = 0;
         if (lane == 0) drawn = __hip_atomic_fetch_add(next_slice, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        const int s_next = __builtin_amdgcn_readfirstlane(drawn);
-        const Slice sl_next = slices[min(s_next, n_slices - 1)];  // clamped: unconditional, in bounds
-        const bool more = s_next < it.slice_end;
-        f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        const int i_next = __builtin_amdgcn_readfirstlane(drawn);
+        const bool more = i_next < n_item_slices;
+        const int i_desc = min(i_next, n_item_slices - 1);  // clamped: the read stays inside the staged part
+        const u32x4_t d_head = desc[2 * i_desc], d_k = desc[2 * i_desc + 1];  // all lanes read the same 32 bytes
+        Acc4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
         // Two batch registers in turn: batch j of a slice sits in register j % 2.  A register is
         // refilled right after its batch is consumed, unconditionally, with the batch two ahead -
         // or, when the slice has no such batch, with batch 0 / 1 of the NEXT slice (parked past
         // the end of the stream when there is none: reads 0, touches no memory).  So the batches
         // of a slice are always on their way one or two batches of work before they are needed,
         // and no wait in the loop ever has more than one younger load in front of it.
-        const uint32_t base = sl.batch0 * 512u, next_base = more ? sl_next.batch0 * 512u : 0xfffff000u;
-        const int batches = (sl.len + kBatchSteps - 1) / kBatchSteps;
-        for (int j = 0, remaining = sl.len; j < batches; j += 2, remaining -= 2 * kBatchSteps) {
+        Cur nxt;
+        nxt.base = more ? (uint32_t)__builtin_amdgcn_readfirstlane((int)d_head.x) * 512u : 0xfffff000u;
+        nxt.len = __builtin_amdgcn_readfirstlane((int)d_head.y);
+        nxt.k = quarter_k((int)d_k.x, (int)d_k.y, (int)d_k.z, (int)d_k.w);
+        const int batches = (cur.len + kBatchSteps - 1) / kBatchSteps;
+        for (int j = 0, remaining = cur.len; j < batches; j += 2, remaining -= 2 * kBatchSteps) {
           quarter_batch(panel, lane_sub, b0, remaining, acc);
-          b0 = load_batch(j + 2 < batches ? base + (uint32_t)(j + 2) * 512u : next_base);
+          b0 = load_batch(j + 2 < batches ? cur.base + (uint32_t)(j + 2) * 512u : nxt.base);
           if (j + 1 < batches) quarter_batch(panel, lane_sub, b1, remaining - kBatchSteps, acc);
-          b1 = load_batch(j + 3 < batches ? base + (uint32_t)(j + 3) * 512u : next_base + 512u);
+          b1 = load_batch(j + 3 < batches ? cur.base + (uint32_t)(j + 3) * 512u : nxt.base + 512u);
         }
         if (batches == 0) {  // an all-empty slice consumed nothing: fetch the next slice's batches here
-          b0 = load_batch(next_base);
-          b1 = load_batch(next_base + 512u);
+          b0 = load_batch(nxt.base);
+          b1 = load_batch(nxt.base + 512u);
         }
-        // row of this lane's quarter; quarters of padding rows are parked beyond the buffer
-        const int k = quarter == 0 ? sl.k[0] : quarter == 1 ? sl.k[1] : quarter == 2 ? sl.k[2] : sl.k[3];
+        // quarters of padding rows are parked beyond the buffer
         const uint32_t moff =
-            k >= 0 ? (((uint32_t)it.p * K + (uint32_t)k) * Tp + tau0) * 4u + lane_sub : 0xfffffff0u;
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4v_t, acc), mr, (int)moff, 0, SWCONV_AUX_M);
+            cur.k >= 0 ? (((uint32_t)it.p * K + (uint32_t)cur.k) * Tp + tau0) * 4u + lane_sub : 0xfffffff0u;
+        const u32x4v_t result = {__float_as_uint(acc.a0), __float_as_uint(acc.a1), __float_as_uint(acc.a2),
+                                 __float_as_uint(acc.a3)};
+        __builtin_amdgcn_raw_buffer_store_b128(result, mr, (int)moff, 0, SWCONV_AUX_M);
         if (!more) break;
-        sl = sl_next;
+        cur = nxt;
       }
     }
     if (!has_next) break;

@@ -82,7 +82,9 @@ SMALL = [
     (1, 1, 1, 1, 1, 2, 1),     # one pixel, one tile
     (1, 2, 3, 3, 3, 4, 0),     # Ho = 1
     (70, 4, 4, 4, 4, 4, 1),    # one tile per image, many images
-    (1, 639, 6, 6, 2, 2, 1),   # largest channel count the panel holds
+    (1, 638, 6, 6, 2, 2, 1),   # largest channel count the panel holds
+    (1, 638, 6, 6, 70, 2, 1),  # ... with more slices per position than its LDS holds descriptors for
+    (2, 6, 9, 9, 1100, 4, 1),  # more slices per position than one work item holds
 ]
 
 

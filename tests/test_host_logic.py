@@ -136,8 +136,10 @@ def test_skewed_weights_pack_and_balance():
     sw.swconv_plan_destroy(pl)
 
 
-@pytest.mark.parametrize("N,C,H,W,K,m", [(1, 3, 5, 5, 1, 2), (64, 384, 13, 13, 384, 4), (3, 639, 6, 6, 7, 2),
-                                         (2, 16, 56, 56, 9, 4), (200, 8, 4, 4, 5, 4)])
+@pytest.mark.parametrize("N,C,H,W,K,m", [(1, 3, 5, 5, 1, 2), (64, 384, 13, 13, 384, 4), (3, 638, 6, 6, 7, 2),
+                                         (2, 16, 56, 56, 9, 4), (200, 8, 4, 4, 5, 4),
+                                         (1, 8, 6, 6, 2100, 2),      # more slices per position than one item holds
+                                         (1, 638, 6, 6, 70, 2)])     # little LDS left for descriptors
 @pytest.mark.parametrize("density", [0.0, 0.1, 1.0])
 def test_schedule_is_a_partition(N, C, H, W, K, m, density):
     P = (m + 2) ** 2
