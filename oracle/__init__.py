@@ -50,6 +50,8 @@ def _load():
         ints8 = [ctypes.c_int] * 8
         lib.oracle_forward_f64.argtypes = ints8 + [f64p, i32p, i32p, f64p, f64p, f64p, f64p]
         lib.oracle_forward_f32.argtypes = ints8 + [f32p, i32p, i32p, f32p, f32p, f32p, f32p]
+        lib.oracle_backward_f64.argtypes = ints8 + [f64p, i32p, i32p, f64p, f64p, f64p, f64p, f64p, f64p]
+        lib.oracle_backward_f32.argtypes = ints8 + [f32p, i32p, i32p, f32p, f32p, f32p, f32p, f32p, f32p]
         lib.oracle_direct_conv_f64.argtypes = [ctypes.c_int] * 7 + [f64p, f64p, f64p]
         lib.oracle_wf_from_spatial_f64.argtypes = [ctypes.c_int] * 4 + [f64p, f64p]
         lib.oracle_winograd_matrices.argtypes = [ctypes.c_int] * 2 + [f64p, f64p, f64p]
@@ -100,6 +102,41 @@ def forward_f32(inp, rowptr, colidx, vals, K, m, r=3, pad=1, want_VM=False):
     """The same loops in float: the timed CPU baseline."""
     return _forward(_load().oracle_forward_f32, np.float32, ctypes.c_float, inp, rowptr, colidx,
                     vals, K, m, r, pad, want_VM)
+
+
+def _backward(fn, dt, ct, inp, rowptr, colidx, vals, dout, K, m, r, pad, want_ZV):
+    inp = np.ascontiguousarray(inp, dtype=dt)
+    N, C, H, W = inp.shape
+    Ho, Wo, th, tw, T = out_shape(N, C, H, W, K, m, r, pad)
+    t = m + r - 1
+    P = t * t
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=dt)
+    dout = np.ascontiguousarray(dout, dtype=dt)
+    assert rowptr.shape == (P * K + 1,) and dout.shape == (N, K, Ho, Wo)
+    assert colidx.shape == vals.shape == (int(rowptr[-1]),)
+    din = np.empty((N, C, H, W), dtype=dt)
+    dvals = np.empty(vals.shape, dtype=dt)
+    dZ = np.empty((P, K, T), dtype=dt) if want_ZV else None
+    dV = np.empty((P, C, T), dtype=dt) if want_ZV else None
+    rc = fn(N, C, H, W, K, m, r, pad, _ptr(inp, ct), _ptr(rowptr, ctypes.c_int32), _ptr(colidx, ctypes.c_int32),
+            _ptr(vals, ct), _ptr(dout, ct), _ptr(dZ, ct), _ptr(dV, ct), _ptr(dvals, ct), _ptr(din, ct))
+    if rc != 0:
+        raise ValueError("oracle backward failed with status %d" % rc)
+    return din, dvals, dZ, dV
+
+
+def backward_f64(inp, rowptr, colidx, vals, dout, K, m, r=3, pad=1, want_ZV=True):
+    """Eq. 5 and Eq. 6 in double precision: (dL/dI, dL/dW_F at the stored entries, dL/dZ, dL/dI_F)."""
+    return _backward(_load().oracle_backward_f64, np.float64, ctypes.c_double, inp, rowptr, colidx, vals, dout, K, m,
+                     r, pad, want_ZV)
+
+
+def backward_f32(inp, rowptr, colidx, vals, dout, K, m, r=3, pad=1, want_ZV=False):
+    """The same loops in float: the timed CPU baseline of the backward pass."""
+    return _backward(_load().oracle_backward_f32, np.float32, ctypes.c_float, inp, rowptr, colidx, vals, dout, K, m,
+                     r, pad, want_ZV)
 
 
 def direct_conv_f64(inp, w, pad):

@@ -17,6 +17,11 @@
 //     definition the layer must reduce to when W_F = G w G^T (Eq. 3).
 //   * Section 3, Eq. 3  - the helper W_F = G w G^T.
 //
+//   * Section 3, Eq. 5 and Eq. 6 - the backward pass of the layer: from dL/dO to
+//     dL/dZ = A dL/dO~ A^T, dL/dW_F(:,:,i,j) = dL/dZ(:,:,i,j) I_F(:,:,i,j)^T (read at
+//     the stored entries of the pruned W_F), dL/dI_F(:,:,i,j) = W_F(:,:,i,j)^T
+//     dL/dZ(:,:,i,j), dL/dI~ = B dL/dI_F B^T and the overlap-add through phi.
+//
 // Every pin that ties these functions to the paper lives in tests/ (brute
 // force on tiny inputs, zero weights, linearity, single non-zero closed form,
 // the overlapped-tiling example of Section 3, permutation invariances).
@@ -203,9 +208,181 @@ int winograd_layer_forward(int N, int C, int H, int W, int K, int m, int r, int 
   return 0;
 }
 
+// Eq. 5 and Eq. 6, in the paper's order.  dout: [N][K][Ho][Wo].  Outputs (each optional):
+// dZ [P][K][T], dV [P][C][T] (dL/dI_F), dvals [nnz] (dL/dW_F at the stored entries, CSR
+// order), din [N][C][H][W].
+template <typename real>
+int winograd_layer_backward(int N, int C, int H, int W, int K, int m, int r, int pad, const real* in,
+                            const int32_t* rowptr, const int32_t* colidx, const real* vals,
+                            const real* dout, real* dZ_out, real* dV_out, real* dvals, real* din) {
+  WinogradMatrices wm;
+  if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || pad < 0) return 1;
+  if (!winograd_matrices(m, r, &wm)) return 2;
+  const int t = wm.t, P = t * t;
+  const int Ho = H + 2 * pad - r + 1, Wo = W + 2 * pad - r + 1;
+  if (Ho < 1 || Wo < 1) return 1;
+  const int th = ceil_div(Ho, m), tw = ceil_div(Wo, m);
+  const int64_t T = (int64_t)N * th * tw;
+
+  std::vector<real> V((size_t)P * C * T), dZ_own, dV_own;
+  real* dZ = dZ_out;
+  real* dV = dV_out;
+  if (!dZ) {
+    dZ_own.resize((size_t)P * K * T);
+    dZ = dZ_own.data();
+  }
+  if (!dV) {
+    dV_own.resize((size_t)P * C * T);
+    dV = dV_own.data();
+  }
+
+  // I_F = B^T I~ B, as in the forward pass (Eq. 5 needs it).
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n) {
+    for (int c = 0; c < C; ++c) {
+      for (int ty = 0; ty < th; ++ty) {
+        for (int tx = 0; tx < tw; ++tx) {
+          const int64_t tau = ((int64_t)n * th + ty) * tw + tx;
+          real d[6][6], Btd[6][6];
+          for (int i = 0; i < t; ++i)
+            for (int j = 0; j < t; ++j) {
+              const int y = ty * m + i - pad, x = tx * m + j - pad;
+              d[i][j] = (y >= 0 && y < H && x >= 0 && x < W) ? in[(((int64_t)n * C + c) * H + y) * W + x] : (real)0;
+            }
+          for (int i = 0; i < t; ++i)
+            for (int j = 0; j < t; ++j) {
+              real s = 0;
+              for (int a = 0; a < t; ++a) s += (real)wm.BT[i][a] * d[a][j];
+              Btd[i][j] = s;
+            }
+          for (int i = 0; i < t; ++i)
+            for (int j = 0; j < t; ++j) {
+              real s = 0;
+              for (int b = 0; b < t; ++b) s += Btd[i][b] * (real)wm.BT[j][b];
+              V[((int64_t)(i * t + j) * C + c) * T + tau] = s;
+            }
+        }
+      }
+    }
+  }
+
+  // Eq. 5, first line: dL/dZ(k,tau,:,:) = A dL/dO~(k,tau,:,:) A^T, where dL/dO~ is dL/dO read
+  // through psi^-1 (zero where the tile reaches past H_o x W_o: those outputs were dropped).
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n) {
+    for (int k = 0; k < K; ++k) {
+      for (int ty = 0; ty < th; ++ty) {
+        for (int tx = 0; tx < tw; ++tx) {
+          const int64_t tau = ((int64_t)n * th + ty) * tw + tx;
+          real g[4][4], Ag[6][4];
+          for (int a = 0; a < m; ++a)
+            for (int b = 0; b < m; ++b) {
+              const int y = ty * m + a, x = tx * m + b;
+              g[a][b] = (y < Ho && x < Wo) ? dout[(((int64_t)n * K + k) * Ho + y) * Wo + x] : (real)0;
+            }
+          for (int i = 0; i < t; ++i)
+            for (int b = 0; b < m; ++b) {
+              real s = 0;
+              for (int a = 0; a < m; ++a) s += (real)wm.AT[a][i] * g[a][b];  // A = (A^T)^T
+              Ag[i][b] = s;
+            }
+          for (int i = 0; i < t; ++i)
+            for (int j = 0; j < t; ++j) {
+              real s = 0;
+              for (int b = 0; b < m; ++b) s += Ag[i][b] * (real)wm.AT[b][j];
+              dZ[((int64_t)(i * t + j) * K + k) * T + tau] = s;
+            }
+        }
+      }
+    }
+  }
+
+  // Eq. 5, second line, at the stored entries: dL/dW_F(k,c,p) = sum_tau dL/dZ(k,tau,p) I_F(c,tau,p).
+  if (dvals) {
+#pragma omp parallel for collapse(2) schedule(dynamic, 8)
+    for (int p = 0; p < P; ++p) {
+      for (int k = 0; k < K; ++k) {
+        const int64_t row = (int64_t)p * K + k;
+        const real* Zrow = dZ + row * T;
+        for (int32_t q = rowptr[row]; q < rowptr[row + 1]; ++q) {
+          const real* Vrow = V.data() + ((int64_t)p * C + colidx[q]) * T;
+          real s = 0;
+          for (int64_t tau = 0; tau < T; ++tau) s += Zrow[tau] * Vrow[tau];
+          dvals[q] = s;
+        }
+      }
+    }
+  }
+
+  // Eq. 6, first line: dL/dI_F(:,:,p) = W_F(:,:,p)^T dL/dZ(:,:,p).
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int p = 0; p < P; ++p) {
+    real* dVp = dV + (int64_t)p * C * T;
+    for (int64_t e = 0; e < (int64_t)C * T; ++e) dVp[e] = 0;
+    for (int k = 0; k < K; ++k) {
+      const int64_t row = (int64_t)p * K + k;
+      const real* Zrow = dZ + row * T;
+      for (int32_t q = rowptr[row]; q < rowptr[row + 1]; ++q) {
+        const real w = vals[q];
+        real* dVrow = dVp + (int64_t)colidx[q] * T;
+        for (int64_t tau = 0; tau < T; ++tau) dVrow[tau] += w * Zrow[tau];
+      }
+    }
+  }
+
+  // Eq. 6, second and third line: dL/dI~ = B dL/dI_F B^T, summed over every (tau, i', j') that phi
+  // maps to the same input pixel.
+  if (din) {
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n) {
+      for (int c = 0; c < C; ++c) {
+        real* plane = din + ((int64_t)n * C + c) * H * W;
+        for (int e = 0; e < H * W; ++e) plane[e] = 0;
+        for (int ty = 0; ty < th; ++ty) {
+          for (int tx = 0; tx < tw; ++tx) {
+            const int64_t tau = ((int64_t)n * th + ty) * tw + tx;
+            real f[6][6], Bf[6][6];
+            for (int i = 0; i < t; ++i)
+              for (int j = 0; j < t; ++j) f[i][j] = dV[((int64_t)(i * t + j) * C + c) * T + tau];
+            for (int a = 0; a < t; ++a)
+              for (int j = 0; j < t; ++j) {
+                real s = 0;
+                for (int i = 0; i < t; ++i) s += (real)wm.BT[i][a] * f[i][j];  // B = (B^T)^T
+                Bf[a][j] = s;
+              }
+            for (int a = 0; a < t; ++a)
+              for (int b = 0; b < t; ++b) {
+                real s = 0;
+                for (int j = 0; j < t; ++j) s += Bf[a][j] * (real)wm.BT[j][b];
+                const int y = ty * m + a - pad, x = tx * m + b - pad;
+                if (y >= 0 && y < H && x >= 0 && x < W) plane[y * W + x] += s;
+              }
+          }
+        }
+      }
+    }
+  }
+  return 0;
+}
+
 }  // namespace
 
 extern "C" {
+
+// Eq. 5 and Eq. 6 in double / float.  dZ, dV, dvals, din may each be NULL.
+int oracle_backward_f64(int N, int C, int H, int W, int K, int m, int r, int pad, const double* in,
+                        const int32_t* rowptr, const int32_t* colidx, const double* vals, const double* dout,
+                        double* dZ, double* dV, double* dvals, double* din) {
+  return winograd_layer_backward<double>(N, C, H, W, K, m, r, pad, in, rowptr, colidx, vals, dout, dZ, dV, dvals,
+                                         din);
+}
+int oracle_backward_f32(int N, int C, int H, int W, int K, int m, int r, int pad, const float* in,
+                        const int32_t* rowptr, const int32_t* colidx, const float* vals, const float* dout,
+                        float* dZ, float* dV, float* dvals, float* din) {
+  return winograd_layer_backward<float>(N, C, H, W, K, m, r, pad, in, rowptr, colidx, vals, dout, dZ, dV, dvals,
+                                        din);
+}
+
 
 // A^T (m x t), B^T (t x t), G (t x r), row-major, into caller buffers.
 int oracle_winograd_matrices(int m, int r, double* AT, double* BT, double* G) {
