@@ -53,27 +53,38 @@ int upload(T** dptr, const std::vector<T>& h) {
 
 }  // namespace
 
+// One position-wise sparse operand of the sparse product kernel in its packed form: P matrices of
+// `rows` x `cols`; the kernel stages panels of `cols` channels and produces `rows` output rows.
+// The forward pass packs W_F (rows = K, cols = C); the backward pass also packs its transpose.
+struct PackedMatrix {
+  int rows = 0, cols = 0;
+  int rows_padded = 0;                // rows rounded up to a multiple of the slice height
+  int waves = 8;                      // waves per workgroup
+  int item_cap = kMaxItemSlices;      // most slices a work item may have (their descriptors are staged in LDS)
+  int n_wgs = 512;                    // persistent workgroups the device can hold at once
+  int n_wgs_used = 0;                 // workgroups the current schedule uses
+  bool packed = false, on_device = false;
+  int64_t nnz = 0, padded_nnz = 0, max_item = 0;
+  std::vector<uint32_t> stream;       // 512-byte batches of (row offset, weight) pairs
+  std::vector<Slice> slices;          // P * rows_padded / kSliceRows
+  std::vector<int32_t> sorted_rows;   // P * rows_padded: original row of each sorted row, -1 = padding
+  std::vector<int32_t> sorted_len;    // P * rows_padded: stored entries of each sorted row
+  std::vector<WorkItem> items;        // in range order
+  std::vector<int32_t> wg_begin;      // n_wgs_used + 1 offsets into items, one range per workgroup
+  std::vector<RangeHeader> ranges;    // the same, as the kernel reads it
+  uint32_t* d_stream = nullptr;
+  Slice* d_slices = nullptr;
+  WorkItem* d_items = nullptr;
+  RangeHeader* d_ranges = nullptr;
+};
+
 struct swconv_plan {
   Geometry g{};
   int m = 0, r = 0, t = 0, P = 0;
-  int waves = 8; // waves per workgroup in the sparse product
-  int item_cap = kMaxItemSlices;  // most slices a work item may have (their descriptors are staged in LDS)
-  int Kp = 0;    // K rounded up to a multiple of the slice height
   int Kq = 0;    // K rounded up to the dense GEMM's row tile
   int n_tau_blocks = 0;
 
-  // host-side packed sparse weights
-  bool have_sparse = false;
-  int64_t nnz = 0, padded_nnz = 0, max_item = 0;
-  std::vector<uint32_t> stream;      // 512-byte batches of (row offset, weight) pairs
-  std::vector<Slice> slices;         // P * Kp / kSliceRows
-  std::vector<int32_t> sorted_rows;  // P * Kp: original row k of each sorted row, -1 = padding
-  std::vector<int32_t> sorted_len;   // P * Kp: stored entries of each sorted row
-  std::vector<WorkItem> items;       // in range order
-  std::vector<int32_t> wg_begin;     // n_wgs_used + 1 offsets into items, one range per workgroup
-  std::vector<RangeHeader> ranges;   // the same, as the kernel reads it
-  int n_wgs = 512;                   // persistent workgroups the device can hold at once
-  int n_wgs_used = 0;                // workgroups the current schedule uses
+  PackedMatrix fw;  // W_F: K rows, panels of C channels (forward)
 
   // host-built index tables of the transform kernels
   std::vector<TileInfo> tiles;        // Tp
@@ -82,12 +93,8 @@ struct swconv_plan {
   BlockImage* d_blocks = nullptr;
 
   // device
-  bool on_device = false, sparse_on_device = false, dense_on_device = false, ran_forward = false;
+  bool on_device = false, dense_on_device = false, ran_forward = false;
   float *dV = nullptr, *dM = nullptr;
-  uint32_t* d_stream = nullptr;
-  Slice* d_slices = nullptr;
-  WorkItem* d_items = nullptr;
-  RangeHeader* d_ranges = nullptr;
   float* d_wdense = nullptr;  // [P][C][Kq]
 };
 
@@ -154,31 +161,35 @@ int launch_output_transform(const swconv_plan* pl, const LaunchTarget& to, float
   return launch_kernel(kern, grid, dim3(256), lds, to, pl->dM, out, pl->d_tiles, pl->d_blocks, pl->g);
 }
 
+// M[p] = A[p] * X[p] for the packed operand `pm`: X has pm.cols rows of Tp tiles per position and
+// x_bytes in all, Y gets pm.rows rows per position.
 template <int NW>
-int launch_spmm_t(const swconv_plan* pl, const LaunchTarget& to) {
-  if (pl->n_wgs_used == 0) return SWCONV_OK;
-  const size_t lds = (size_t)pl->g.C * kTileBlock * sizeof(float) + kSpmmLdsExtra + (size_t)pl->item_cap * sizeof(Slice);
+int launch_spmm_t(const swconv_plan* pl, const PackedMatrix& pm, const LaunchTarget& to, const float* X,
+                  uint32_t x_bytes, float* Y, uint32_t y_bytes) {
+  if (pm.n_wgs_used == 0) return SWCONV_OK;
+  const size_t lds = (size_t)pm.cols * kTileBlock * sizeof(float) + kSpmmLdsExtra + (size_t)pm.item_cap * sizeof(Slice);
   auto kern = spmm_kernel<NW>;
   static bool attr_set = false;
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  return launch_kernel(kern, dim3(pl->n_wgs_used), dim3(NW * 64), lds, to, pl->dV, pl->dM, pl->d_stream,
-                       (uint32_t)(pl->stream.size() * sizeof(uint32_t)), pl->d_slices, (int)pl->slices.size(),
-                       pl->d_items, pl->d_ranges, pl->n_wgs_used, pl->g.C, pl->g.K, pl->g.Tp, pl->g.m_bytes,
-                       pl->g.v_bytes);
+  return launch_kernel(kern, dim3(pm.n_wgs_used), dim3(NW * 64), lds, to, X, Y, pm.d_stream,
+                       (uint32_t)(pm.stream.size() * sizeof(uint32_t)), pm.d_slices, (int)pm.slices.size(),
+                       pm.d_items, pm.d_ranges, pm.n_wgs_used, pm.cols, pm.rows, pl->g.Tp, y_bytes, x_bytes);
 }
 
-int launch_spmm(const swconv_plan* pl, const LaunchTarget& to) {
-  if (pl->waves == 12) return launch_spmm_t<12>(pl, to);
-  return pl->waves == 16 ? launch_spmm_t<16>(pl, to) : launch_spmm_t<8>(pl, to);
+int launch_spmm(const swconv_plan* pl, const PackedMatrix& pm, const LaunchTarget& to, const float* X,
+                uint32_t x_bytes, float* Y, uint32_t y_bytes) {
+  if (pm.waves == 12) return launch_spmm_t<12>(pl, pm, to, X, x_bytes, Y, y_bytes);
+  return pm.waves == 16 ? launch_spmm_t<16>(pl, pm, to, X, x_bytes, Y, y_bytes)
+                        : launch_spmm_t<8>(pl, pm, to, X, x_bytes, Y, y_bytes);
 }
 
 int launch_stage(const swconv_plan* pl, const LaunchTarget& to, int stage, const float* in, float* out) {
   switch (stage) {
     case 0: return pl->m == 2 ? launch_input_transform<2>(pl, to, in) : launch_input_transform<4>(pl, to, in);
-    case 1: return launch_spmm(pl, to);
+    case 1: return launch_spmm(pl, pl->fw, to, pl->dV, pl->g.v_bytes, pl->dM, pl->g.m_bytes);
     default: return pl->m == 2 ? launch_output_transform<2>(pl, to, out) : launch_output_transform<4>(pl, to, out);
   }
 }
@@ -265,16 +276,16 @@ int validate_csr(const swconv_plan* pl, const int32_t* rowptr, const int32_t* co
 // range is found by bisection.  A range touches at most a few panels, consecutive ranges share
 // panels and weights (and, through xcd_contiguous_id, an XCD's L2), and the split adapts by
 // itself to positions of very different density.
-void build_schedule(swconv_plan* pl) {
-  const int P = pl->P, spp = pl->Kp / kSliceRows, ntb = pl->n_tau_blocks;
+void build_schedule(PackedMatrix* pm, int P, int ntb) {
+  const int spp = pm->rows_padded / kSliceRows;
   // Costs in units of the time a workgroup spends on one step of a slice (four 16-byte LDS reads
   // per wave quarter-row, 16 FMAs per lane).  Fitted on MI355X over uniform and skewed patterns: a
   // slice costs about 32 steps on top of its own (draw, descriptor, first batches, row store),
   // staging a panel about 20 steps per KiB.
   const int64_t slice_ovh = env_int("SWCONV_SPMM_SLICE_COST", 32);
-  const int64_t panel_kib = ((int64_t)pl->g.C * kTileBlock * (int64_t)sizeof(float) + 1023) / 1024;
+  const int64_t panel_kib = ((int64_t)pm->cols * kTileBlock * (int64_t)sizeof(float) + 1023) / 1024;
   const int64_t panel_cost = (int64_t)env_int("SWCONV_SPMM_PANEL_COST_PER_KIB", 20) * panel_kib;
-  const int wgs_max = std::max(1, pl->n_wgs);
+  const int wgs_max = std::max(1, pm->n_wgs);
 
   auto cut = [&](int64_t budget, std::vector<WorkItem>* items, std::vector<int32_t>* begin) -> int {
     int wgs = 0;
@@ -294,18 +305,18 @@ void build_schedule(swconv_plan* pl) {
         const int s_end = s + spp;
         while (s < s_end) {
           // a new item in the current workgroup: pay the panel, then take slices while they fit
-          if (open_wg && acc + panel_cost + pl->slices[s].len + slice_ovh > budget) close_wg();
+          if (open_wg && acc + panel_cost + pm->slices[s].len + slice_ovh > budget) close_wg();
           open_wg = true;
           acc += panel_cost;
           const int s0 = s;
-          while (s < s_end && s - s0 < pl->item_cap) {
-            const int64_t c = pl->slices[s].len + slice_ovh;
+          while (s < s_end && s - s0 < pm->item_cap) {
+            const int64_t c = pm->slices[s].len + slice_ovh;
             if (s > s0 && acc + c > budget) break;
             acc += c;
             ++s;
           }
           if (items) items->push_back(WorkItem{p, tb, s0, s});
-          if (s < s_end && s - s0 < pl->item_cap) close_wg();  // the budget, not the item cap, ended the item
+          if (s < s_end && s - s0 < pm->item_cap) close_wg();  // the budget, not the item cap, ended the item
         }
       }
     close_wg();
@@ -313,7 +324,7 @@ void build_schedule(swconv_plan* pl) {
   };
 
   int64_t total = 0, biggest = 0;
-  for (const Slice& sl : pl->slices) {
+  for (const Slice& sl : pm->slices) {
     total += sl.len + slice_ovh;
     biggest = std::max<int64_t>(biggest, sl.len + slice_ovh);
   }
@@ -323,20 +334,20 @@ void build_schedule(swconv_plan* pl) {
     const int64_t mid = lo + (hi - lo) / 2;
     if (cut(mid, nullptr, nullptr) <= wgs_max) hi = mid; else lo = mid + 1;
   }
-  pl->n_wgs_used = cut(lo, &pl->items, &pl->wg_begin);
-  pl->ranges.assign((size_t)pl->n_wgs_used, RangeHeader{});
-  for (int b = 0; b < pl->n_wgs_used; ++b) {
-    RangeHeader& h = pl->ranges[b];
-    h.item_begin = pl->wg_begin[b];
-    h.item_end = pl->wg_begin[b + 1];
-    h.first = pl->items[h.item_begin];
+  pm->n_wgs_used = cut(lo, &pm->items, &pm->wg_begin);
+  pm->ranges.assign((size_t)pm->n_wgs_used, RangeHeader{});
+  for (int b = 0; b < pm->n_wgs_used; ++b) {
+    RangeHeader& h = pm->ranges[b];
+    h.item_begin = pm->wg_begin[b];
+    h.item_end = pm->wg_begin[b + 1];
+    h.first = pm->items[h.item_begin];
   }
-  pl->max_item = 0;
-  for (int b = 0; b < pl->n_wgs_used; ++b) {
+  pm->max_item = 0;
+  for (int b = 0; b < pm->n_wgs_used; ++b) {
     int64_t steps = 0;
-    for (int i = pl->wg_begin[b]; i < pl->wg_begin[b + 1]; ++i)
-      for (int sidx = pl->items[i].slice_begin; sidx < pl->items[i].slice_end; ++sidx) steps += pl->slices[sidx].len;
-    pl->max_item = std::max(pl->max_item, steps * kSliceRows);
+    for (int i = pm->wg_begin[b]; i < pm->wg_begin[b + 1]; ++i)
+      for (int sidx = pm->items[i].slice_begin; sidx < pm->items[i].slice_end; ++sidx) steps += pm->slices[sidx].len;
+    pm->max_item = std::max(pm->max_item, steps * kSliceRows);
   }
 }
 
@@ -346,75 +357,170 @@ inline size_t stream_entry(uint32_t batch0, int q, int32_t e) {
   return ((size_t)batch0 + (size_t)(e / kBatchSteps)) * 128 + ((size_t)q * kBatchSteps + (size_t)(e % kBatchSteps)) * 2;
 }
 
-// Re-pack per-position CSR into the sliced layout and build the schedule.
-void pack_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, const float* vals) {
-  const int P = pl->P, K = pl->g.K, Kp = pl->Kp;
-  const int slices_per_pos = Kp / kSliceRows;
-  pl->nnz = rowptr[(int64_t)P * K];
-  pl->sorted_rows.assign((size_t)P * Kp, -1);
-  pl->sorted_len.assign((size_t)P * Kp, 0);
-  pl->slices.assign((size_t)P * slices_per_pos, Slice{});
+// Shape-dependent launch parameters of a packed operand with `rows` x `cols` matrices; false when
+// the panel of `cols` channels (256 bytes each), the slice counter and the descriptors of at least
+// kMinItemSlices slices do not fit LDS.
+bool configure_packed(PackedMatrix* pm, int rows, int cols) {
+  pm->rows = rows;
+  pm->cols = cols;
+  pm->rows_padded = (rows + kSliceRows - 1) / kSliceRows * kSliceRows;
+  const int64_t panel_bytes = (int64_t)cols * kTileBlock * (int64_t)sizeof(float);
+  const int64_t desc_room = (kMaxLdsBytes - kSpmmLdsExtra - panel_bytes) / (int64_t)sizeof(Slice);
+  if (desc_room < kMinItemSlices) return false;
+  pm->item_cap = (int)std::min<int64_t>(std::min<int64_t>(kMaxItemSlices, desc_room), pm->rows_padded / kSliceRows);
+  // two workgroups of 12 waves per CU while two panels fit LDS (six waves per SIMD hide the LDS and
+  // draw latencies better than four), else one of 16
+  const int64_t wg_lds = panel_bytes + kSpmmLdsExtra + (int64_t)pm->item_cap * (int64_t)sizeof(Slice);
+  const int dflt_waves = wg_lds * 2 > kMaxLdsBytes ? 16 : 12;
+  pm->waves = env_int("SWCONV_SPMM_WAVES", dflt_waves);
+  if (pm->waves != 8 && pm->waves != 12 && pm->waves != 16) pm->waves = dflt_waves;
+  // a thread stages at most kPanelPieces 16-byte pieces of a panel
+  if (panel_bytes > (int64_t)kPanelPieces * pm->waves * 64 * 16) pm->waves = 16;
+  return true;
+}
 
-  std::vector<int32_t> order(K);
+// Persistent workgroups the device holds at once: as many per CU as the operand's LDS allows.
+void size_grid(PackedMatrix* pm) {
+  int cus = 256, ndev = 0, dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0 && hipGetDevice(&dev) == hipSuccess &&
+      hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
+    cus = prop.multiProcessorCount;
+  else
+    (void)hipGetLastError();
+  const size_t wg_lds = (size_t)pm->cols * kTileBlock * sizeof(float) + kSpmmLdsExtra + (size_t)pm->item_cap * sizeof(Slice);
+  const int per_cu = std::max<int>(1, std::min<int>(32 / pm->waves, (int)(kMaxLdsBytes / wg_lds)));
+  pm->n_wgs = std::max(1, env_int("SWCONV_SPMM_WGS", cus * per_cu));
+}
+
+// Re-pack P row-major CSR matrices (rows (p, row) -> p * rows + row, global offsets) into the sliced
+// layout and build the schedule.
+void pack_matrix(PackedMatrix* pm, int P, int ntb, const int32_t* rowptr, const int32_t* colidx, const float* vals) {
+  const int R = pm->rows, Rp = pm->rows_padded;
+  const int slices_per_pos = Rp / kSliceRows;
+  pm->nnz = rowptr[(int64_t)P * R];
+  pm->sorted_rows.assign((size_t)P * Rp, -1);
+  pm->sorted_len.assign((size_t)P * Rp, 0);
+  pm->slices.assign((size_t)P * slices_per_pos, Slice{});
+
+  std::vector<int32_t> order(R);
   uint64_t cursor = 0;  // 512-byte batches
-  pl->padded_nnz = 0;
+  pm->padded_nnz = 0;
   for (int p = 0; p < P; ++p) {
-    const int32_t* rp = rowptr + (int64_t)p * K;
+    const int32_t* rp = rowptr + (int64_t)p * R;
     std::iota(order.begin(), order.end(), 0);
     std::stable_sort(order.begin(), order.end(),
                      [&](int32_t a, int32_t b) { return rp[a + 1] - rp[a] > rp[b + 1] - rp[b]; });
-    for (int i = 0; i < K; ++i) {
-      pl->sorted_rows[(size_t)p * Kp + i] = order[i];
-      pl->sorted_len[(size_t)p * Kp + i] = rp[order[i] + 1] - rp[order[i]];
+    for (int i = 0; i < R; ++i) {
+      pm->sorted_rows[(size_t)p * Rp + i] = order[i];
+      pm->sorted_len[(size_t)p * Rp + i] = rp[order[i] + 1] - rp[order[i]];
     }
     for (int s = 0; s < slices_per_pos; ++s) {
-      Slice& sl = pl->slices[(size_t)p * slices_per_pos + s];
+      Slice& sl = pm->slices[(size_t)p * slices_per_pos + s];
       sl.p = p;
-      sl.row0 = p * Kp + s * kSliceRows;
+      sl.row0 = p * Rp + s * kSliceRows;
       sl.batch0 = (uint32_t)cursor;
-      for (int r = 0; r < kSliceRows; ++r) sl.k[r] = pl->sorted_rows[sl.row0 + r];
+      for (int r = 0; r < kSliceRows; ++r) sl.k[r] = pm->sorted_rows[sl.row0 + r];
       // rows are sorted: the first is the longest; whole groups of steps
-      sl.len = (pl->sorted_len[sl.row0] + kStepGroup - 1) / kStepGroup * kStepGroup;
+      sl.len = (pm->sorted_len[sl.row0] + kStepGroup - 1) / kStepGroup * kStepGroup;
       cursor += (sl.len + kBatchSteps - 1) / kBatchSteps;
-      pl->padded_nnz += (int64_t)sl.len * kSliceRows;
+      pm->padded_nnz += (int64_t)sl.len * kSliceRows;
     }
   }
-  // an entry is (byte offset of the panel row of column c, weight); padding = row 0, weight +0.0f.
+  // an entry is (byte offset of the panel row of its column, weight); padding = row 0, weight +0.0f.
   // The kernel addresses the stream with 32-bit byte offsets and fetches up to two batches past a
   // slice's end: two spare batches keep even those inside the allocation.
   cursor += 2;
   if (cursor * 512 >= ((uint64_t)1 << 32) - 4096) throw std::bad_alloc();
   const uint32_t row_bytes = (uint32_t)kTileBlock * sizeof(float);
-  pl->stream.assign((size_t)cursor * 128, 0u);
-  for (size_t s = 0; s < pl->slices.size(); ++s) {
-    const Slice& sl = pl->slices[s];
-    const int32_t* rp = rowptr + (int64_t)sl.p * K;
+  pm->stream.assign((size_t)cursor * 128, 0u);
+  for (size_t s = 0; s < pm->slices.size(); ++s) {
+    const Slice& sl = pm->slices[s];
+    const int32_t* rp = rowptr + (int64_t)sl.p * R;
     for (int r = 0; r < kSliceRows; ++r) {
-      const int k = pl->sorted_rows[sl.row0 + r];
-      if (k < 0) continue;
-      const int32_t q0 = rp[k], len = rp[k + 1] - rp[k];
+      const int row = pm->sorted_rows[sl.row0 + r];
+      if (row < 0) continue;
+      const int32_t q0 = rp[row], len = rp[row + 1] - rp[row];
       for (int32_t e = 0; e < len; ++e) {
-        uint32_t* entry = &pl->stream[stream_entry(sl.batch0, r, e)];
+        uint32_t* entry = &pm->stream[stream_entry(sl.batch0, r, e)];
         entry[0] = (uint32_t)colidx[q0 + e] * row_bytes;
         std::memcpy(&entry[1], &vals[q0 + e], sizeof(float));
       }
     }
   }
-  build_schedule(pl);
-  pl->have_sparse = true;
+  build_schedule(pm, P, ntb);
+  pm->packed = true;
 }
 
-int upload_sparse(swconv_plan* pl) {
-  int rc = ensure_workspace(pl);
-  if (rc) return rc;
-  pl->sparse_on_device = false;
-  if ((rc = upload(&pl->d_stream, pl->stream))) return rc;
-  if ((rc = upload(&pl->d_slices, pl->slices))) return rc;
-  if ((rc = upload(&pl->d_items, pl->items))) return rc;
-  if ((rc = upload(&pl->d_ranges, pl->ranges))) return rc;
+// The inverse of pack_matrix: back to CSR, padding dropped, rows in their original order.
+void unpack_matrix(const PackedMatrix& pm, int P, int32_t* rowptr, int32_t* colidx, float* vals) {
+  const int R = pm.rows, Rp = pm.rows_padded;
+  rowptr[0] = 0;
+  std::vector<int32_t> len((size_t)P * R, 0);
+  for (int p = 0; p < P; ++p)
+    for (int i = 0; i < Rp; ++i) {
+      const int row = pm.sorted_rows[(size_t)p * Rp + i];
+      if (row >= 0) len[(size_t)p * R + row] = pm.sorted_len[(size_t)p * Rp + i];
+    }
+  for (int64_t i = 0; i < (int64_t)P * R; ++i) rowptr[i + 1] = rowptr[i] + len[i];
+  for (const Slice& sl : pm.slices)
+    for (int r = 0; r < kSliceRows; ++r) {
+      const int row = pm.sorted_rows[sl.row0 + r];
+      if (row < 0) continue;
+      const int32_t q0 = rowptr[(int64_t)sl.p * R + row];
+      for (int32_t e = 0; e < pm.sorted_len[sl.row0 + r]; ++e) {
+        const uint32_t* entry = &pm.stream[stream_entry(sl.batch0, r, e)];
+        colidx[q0 + e] = (int32_t)(entry[0] / ((uint32_t)kTileBlock * sizeof(float)));
+        std::memcpy(&vals[q0 + e], &entry[1], sizeof(float));
+      }
+    }
+}
+
+int upload_packed(PackedMatrix* pm) {
+  int rc;
+  pm->on_device = false;
+  if ((rc = upload(&pm->d_stream, pm->stream))) return rc;
+  if ((rc = upload(&pm->d_slices, pm->slices))) return rc;
+  if ((rc = upload(&pm->d_items, pm->items))) return rc;
+  if ((rc = upload(&pm->d_ranges, pm->ranges))) return rc;
   HIP_TRY(hipDeviceSynchronize());
-  pl->sparse_on_device = true;
+  pm->on_device = true;
   return SWCONV_OK;
+}
+
+void free_packed(PackedMatrix* pm) {
+  void* bufs[] = {pm->d_stream, pm->d_slices, pm->d_items, pm->d_ranges};
+  for (void* b : bufs)
+    if (b) (void)hipFree(b);
+  pm->d_stream = nullptr;
+  pm->d_slices = nullptr;
+  pm->d_items = nullptr;
+  pm->d_ranges = nullptr;
+  pm->on_device = false;
+}
+
+// True when the schedule of `pm` is a partition of its (position, tile block, slice) units.
+bool schedule_is_partition(const PackedMatrix& pm, int P, int ntb) {
+  const int spp = pm.rows_padded / kSliceRows;
+  std::vector<uint8_t> seen((size_t)P * ntb * spp, 0);
+  if ((int)pm.wg_begin.size() != pm.n_wgs_used + 1 || pm.wg_begin[0] != 0 ||
+      pm.wg_begin.back() != (int32_t)pm.items.size() || pm.n_wgs_used > std::max(1, pm.n_wgs))
+    return false;
+  for (int b = 0; b < pm.n_wgs_used; ++b)
+    if (pm.wg_begin[b + 1] <= pm.wg_begin[b]) return false;  // no idle workgroup is launched
+  for (const WorkItem& w : pm.items) {
+    if (w.p < 0 || w.p >= P || w.tau_block < 0 || w.tau_block >= ntb) return false;
+    if (w.slice_begin < w.p * spp || w.slice_end > (w.p + 1) * spp || w.slice_begin >= w.slice_end) return false;
+    if (w.slice_end - w.slice_begin > pm.item_cap) return false;  // descriptors must fit their LDS area
+    for (int sidx = w.slice_begin; sidx < w.slice_end; ++sidx) {
+      uint8_t& f = seen[((size_t)w.p * ntb + w.tau_block) * spp + (sidx - w.p * spp)];
+      if (f) return false;
+      f = 1;
+    }
+  }
+  for (uint8_t f : seen)
+    if (!f) return false;
+  return true;
 }
 
 int copy_padded_to_host(const float* dsrc, float* hdst, size_t rows, int T, int Tp) {
@@ -457,29 +563,14 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
 
   swconv_plan* pl = new (std::nothrow) swconv_plan();
   if (!pl) return SWCONV_ENOMEM;
-  // the sparse product stages a C x 64 panel (256 bytes per channel), its slice counter and the
-  // descriptors of at least kMinItemSlices slices in LDS
-  const int64_t panel_bytes = (int64_t)C * kTileBlock * (int64_t)sizeof(float);
-  const int64_t desc_room = (kMaxLdsBytes - kSpmmLdsExtra - panel_bytes) / (int64_t)sizeof(Slice);
-  if (desc_room < kMinItemSlices) {
+  if (!configure_packed(&pl->fw, K, C)) {  // the C x 64 panel of the sparse product must fit LDS
     delete pl;
     return SWCONV_EUNSUPPORTED;
   }
-  pl->item_cap = (int)std::min<int64_t>(kMaxItemSlices, desc_room);
   pl->m = m;
   pl->r = r;
   pl->t = t;
   pl->P = P;
-  // two workgroups of 12 waves per CU while two panels fit LDS (six waves per SIMD hide the LDS and
-  // draw latencies better than four), else one of 16
-  const int64_t wg_lds = panel_bytes + kSpmmLdsExtra + (int64_t)std::min<int64_t>(pl->item_cap, (K + kSliceRows - 1) / kSliceRows) * (int64_t)sizeof(Slice);
-  const int dflt_waves = wg_lds * 2 > kMaxLdsBytes ? 16 : 12;
-  pl->waves = env_int("SWCONV_SPMM_WAVES", dflt_waves);
-  if (pl->waves != 8 && pl->waves != 12 && pl->waves != 16) pl->waves = dflt_waves;
-  // a thread stages at most kPanelPieces 16-byte pieces of a panel
-  if (panel_bytes > (int64_t)kPanelPieces * pl->waves * 64 * 16) pl->waves = 16;
-  pl->Kp = (K + kSliceRows - 1) / kSliceRows * kSliceRows;
-  pl->item_cap = std::min(pl->item_cap, pl->Kp / kSliceRows);
   Geometry& g = pl->g;
   g.N = N; g.C = C; g.H = H; g.W = W; g.K = K; g.pad = pad;
   g.Ho = (int)Ho; g.Wo = (int)Wo; g.th = (int)th; g.tw = (int)tw; g.tpi = (int)(th * tw);
@@ -520,9 +611,10 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
 
 void swconv_plan_destroy(swconv_plan* pl) {
   if (!pl) return;
-  void* bufs[] = {pl->dV, pl->dM, pl->d_stream, pl->d_slices, pl->d_items, pl->d_ranges, pl->d_wdense, pl->d_tiles, pl->d_blocks};
+  void* bufs[] = {pl->dV, pl->dM, pl->d_wdense, pl->d_tiles, pl->d_blocks};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
+  free_packed(&pl->fw);
   delete pl;
 }
 
@@ -530,32 +622,21 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   if (!pl) return SWCONV_EINVAL;
   int rc = validate_csr(pl, rowptr, colidx, vals);
   if (rc) return rc;
-  {
-    // persistent workgroups the device holds at once: as many per CU as the panel's LDS allows
-    int cus = 256, ndev = 0, dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0 && hipGetDevice(&dev) == hipSuccess &&
-        hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
-      cus = prop.multiProcessorCount;
-    else
-      (void)hipGetLastError();
-    const size_t panel_bytes = (size_t)pl->g.C * kTileBlock * sizeof(float) + kSpmmLdsExtra + (size_t)pl->item_cap * sizeof(Slice);
-    const int per_cu = std::max<int>(1, std::min<int>(32 / pl->waves, (int)(kMaxLdsBytes / panel_bytes)));
-    pl->n_wgs = std::max(1, env_int("SWCONV_SPMM_WGS", cus * per_cu));
-  }
+  size_grid(&pl->fw);
   try {
-    pack_weights(pl, rowptr, colidx, vals);
+    pack_matrix(&pl->fw, pl->P, pl->n_tau_blocks, rowptr, colidx, vals);
   } catch (const std::bad_alloc&) {
-    pl->have_sparse = false;
-    pl->sparse_on_device = false;
+    pl->fw.packed = false;
+    pl->fw.on_device = false;
     return SWCONV_ENOMEM;
   }
-  return upload_sparse(pl);
+  if ((rc = ensure_workspace(pl))) return rc;
+  return upload_packed(&pl->fw);
 }
 
 int swconv_forward(swconv_plan* pl, void* hip_stream, const float* in_dev, float* out_dev) {
   if (!pl || !in_dev || !out_dev) return SWCONV_EINVAL;
-  if (!pl->sparse_on_device) return SWCONV_ESTATE;
+  if (!pl->fw.on_device) return SWCONV_ESTATE;
   const LaunchTarget to{(hipStream_t)hip_stream, nullptr, nullptr};
   for (int stage = 0; stage < 3; ++stage) {
     int rc = launch_stage(pl, to, stage, in_dev, out_dev);
@@ -568,7 +649,7 @@ int swconv_forward(swconv_plan* pl, void* hip_stream, const float* in_dev, float
 int swconv_profile_forward(swconv_plan* pl, void* hip_stream, const float* in_dev, float* out_dev, int iters,
                            float* stage_ms) {
   if (!pl || !in_dev || !out_dev || !stage_ms || iters < 1) return SWCONV_EINVAL;
-  if (!pl->sparse_on_device) return SWCONV_ESTATE;
+  if (!pl->fw.on_device) return SWCONV_ESTATE;
   hipStream_t st = (hipStream_t)hip_stream;
   // one (start, stop) pair per kernel launch; the events take the kernel's own time stamps
   std::vector<hipEvent_t> ev((size_t)iters * 6, nullptr);
@@ -617,55 +698,16 @@ int swconv_debug_copy_M(swconv_plan* pl, float* M_host) {
 
 int swconv_debug_export_weights(swconv_plan* pl, int32_t* rowptr, int32_t* colidx, float* vals) {
   if (!pl || !rowptr) return SWCONV_EINVAL;
-  if (!pl->have_sparse) return SWCONV_ESTATE;
-  if (pl->nnz > 0 && (!colidx || !vals)) return SWCONV_EINVAL;
-  const int P = pl->P, K = pl->g.K, Kp = pl->Kp;
-  // row lengths back in original order -> rowptr
-  rowptr[0] = 0;
-  std::vector<int32_t> len((size_t)P * K, 0);
-  for (int p = 0; p < P; ++p)
-    for (int i = 0; i < Kp; ++i) {
-      const int k = pl->sorted_rows[(size_t)p * Kp + i];
-      if (k >= 0) len[(size_t)p * K + k] = pl->sorted_len[(size_t)p * Kp + i];
-    }
-  for (int64_t i = 0; i < (int64_t)P * K; ++i) rowptr[i + 1] = rowptr[i] + len[i];
-  for (const Slice& sl : pl->slices)
-    for (int r = 0; r < kSliceRows; ++r) {
-      const int k = pl->sorted_rows[sl.row0 + r];
-      if (k < 0) continue;
-      const int32_t q0 = rowptr[(int64_t)sl.p * K + k];
-      for (int32_t e = 0; e < pl->sorted_len[sl.row0 + r]; ++e) {
-        const uint32_t* entry = &pl->stream[stream_entry(sl.batch0, r, e)];
-        colidx[q0 + e] = (int32_t)(entry[0] / ((uint32_t)kTileBlock * sizeof(float)));
-        std::memcpy(&vals[q0 + e], &entry[1], sizeof(float));
-      }
-    }
+  if (!pl->fw.packed) return SWCONV_ESTATE;
+  if (pl->fw.nnz > 0 && (!colidx || !vals)) return SWCONV_EINVAL;
+  unpack_matrix(pl->fw, pl->P, rowptr, colidx, vals);
   return SWCONV_OK;
 }
 
 int swconv_debug_check_schedule(const swconv_plan* pl) {
   if (!pl) return SWCONV_EINVAL;
-  if (!pl->have_sparse) return SWCONV_ESTATE;
-  const int spp = pl->Kp / kSliceRows, ntb = pl->n_tau_blocks;
-  std::vector<uint8_t> seen((size_t)pl->P * ntb * spp, 0);
-  if ((int)pl->wg_begin.size() != pl->n_wgs_used + 1 || pl->wg_begin[0] != 0 ||
-      pl->wg_begin.back() != (int32_t)pl->items.size() || pl->n_wgs_used > std::max(1, pl->n_wgs))
-    return SWCONV_EINVAL;
-  for (int b = 0; b < pl->n_wgs_used; ++b)
-    if (pl->wg_begin[b + 1] <= pl->wg_begin[b]) return SWCONV_EINVAL;  // no idle workgroup is launched
-  for (const WorkItem& w : pl->items) {
-    if (w.p < 0 || w.p >= pl->P || w.tau_block < 0 || w.tau_block >= ntb) return SWCONV_EINVAL;
-    if (w.slice_begin < w.p * spp || w.slice_end > (w.p + 1) * spp || w.slice_begin >= w.slice_end) return SWCONV_EINVAL;
-    if (w.slice_end - w.slice_begin > pl->item_cap) return SWCONV_EINVAL;  // descriptors must fit their LDS area
-    for (int sidx = w.slice_begin; sidx < w.slice_end; ++sidx) {
-      uint8_t& f = seen[((size_t)w.p * ntb + w.tau_block) * spp + (sidx - w.p * spp)];
-      if (f) return SWCONV_EINVAL;
-      f = 1;
-    }
-  }
-  for (uint8_t f : seen)
-    if (!f) return SWCONV_EINVAL;
-  return SWCONV_OK;
+  if (!pl->fw.packed) return SWCONV_ESTATE;
+  return schedule_is_partition(pl->fw, pl->P, pl->n_tau_blocks) ? SWCONV_OK : SWCONV_EINVAL;
 }
 
 int swconv_plan_sizes(const swconv_plan* pl, int* P, int64_t* T, int* Ho, int* Wo) {
@@ -680,11 +722,11 @@ int swconv_plan_sizes(const swconv_plan* pl, int* P, int64_t* T, int* Ho, int* W
 int swconv_plan_weight_stats(const swconv_plan* pl, int64_t* nnz, int64_t* padded_nnz, int* work_items,
                              int64_t* max_item) {
   if (!pl) return SWCONV_EINVAL;
-  if (!pl->have_sparse) return SWCONV_ESTATE;
-  if (nnz) *nnz = pl->nnz;
-  if (padded_nnz) *padded_nnz = pl->padded_nnz;
-  if (work_items) *work_items = (int)pl->items.size();
-  if (max_item) *max_item = pl->max_item;
+  if (!pl->fw.packed) return SWCONV_ESTATE;
+  if (nnz) *nnz = pl->fw.nnz;
+  if (padded_nnz) *padded_nnz = pl->fw.padded_nnz;
+  if (work_items) *work_items = (int)pl->fw.items.size();
+  if (max_item) *max_item = pl->fw.max_item;
   return SWCONV_OK;
 }
 
