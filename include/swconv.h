@@ -114,6 +114,32 @@ int swconv_set_weights_dense(swconv_plan* plan, const float* wf);
 int swconv_forward_dense(swconv_plan* plan, void* hip_stream, const float* in_dev, float* out_dev);
 
 /*
+ * Backward pass of the layer (Section 3, Eq. 5 and Eq. 6) for L a scalar loss: from dL/dO to
+ *   dL/dZ(k,tau) = A dL/dO~(k,tau) A^T,          dL/dO~ = dL/dO read through psi^-1 (zero where a tile
+ *                                                reaches past Ho x Wo: those outputs were dropped)
+ *   dL/dW_F(:,:,p) = dL/dZ(:,:,p) I_F(:,:,p)^T,  at the stored entries of the pruned W_F only
+ *   dL/dI_F(:,:,p) = W_F(:,:,p)^T dL/dZ(:,:,p),  dL/dI~ = B dL/dI_F B^T,  dL/dI = overlap-add through phi
+ * enqueued on `hip_stream`.
+ *   in_dev     DEVICE, N x C x H x W, the input of the forward pass (I_F is recomputed from it)
+ *   dout_dev   DEVICE, N x K x Ho x Wo, dL/dO
+ *   din_dev    DEVICE, N x C x H x W or NULL: dL/dI, every element overwritten
+ *   dvals_dev  DEVICE, nnz floats or NULL: dL/dW_F at the stored entries, in the order of the CSR
+ *              arrays given to swconv_set_weights
+ * The first call after swconv_set_weights also packs the transposed weights on the host and blocks.
+ * Overwrites the plan's workspaces (swconv_debug_copy_V / _M then see backward data).
+ * Errors: EINVAL, ESTATE (no weights), EUNSUPPORTED (K > 638: the panels of dL/dZ do not fit LDS; or
+ * N*C > 65535), ENOMEM, EHIP.
+ */
+int swconv_backward(swconv_plan* plan, void* hip_stream, const float* in_dev, const float* dout_dev, float* din_dev,
+                    float* dvals_dev);
+
+/* Test hooks: intermediates of the last backward pass, canonical layouts.
+ *   dZ_host  HOST, [P][K][T] (dL/dZ)      dV_host  HOST, [P][C][T] (dL/dI_F)
+ * Errors: ESTATE when no backward pass has run; EHIP. */
+int swconv_debug_copy_dZ(swconv_plan* plan, float* dZ_host);
+int swconv_debug_copy_dV(swconv_plan* plan, float* dV_host);
+
+/*
  * Measurement helper: run `iters` sparse forward passes on `hip_stream`, every kernel launched
  * with a pair of HIP events that take the kernel's own start and end time stamps on that stream
  * (no extra packets between the kernels), synchronise, and return the mean duration of each

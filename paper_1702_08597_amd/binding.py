@@ -17,6 +17,7 @@ EXPORTS = [
     "swconv_forward", "swconv_set_weights_dense", "swconv_forward_dense", "swconv_profile_forward",
     "swconv_debug_copy_V", "swconv_debug_copy_M", "swconv_debug_export_weights", "swconv_plan_sizes",
     "swconv_plan_weight_stats", "swconv_debug_check_schedule",
+    "swconv_backward", "swconv_debug_copy_dZ", "swconv_debug_copy_dV",
 ]
 
 _lib = None
@@ -56,6 +57,9 @@ def lib():
         L.swconv_plan_weight_stats.argtypes = [_vp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
                                                ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int64)]
         L.swconv_debug_check_schedule.argtypes = [_vp]
+        L.swconv_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
+        L.swconv_debug_copy_dZ.argtypes = [_vp, _f32p]
+        L.swconv_debug_copy_dV.argtypes = [_vp, _f32p]
         _lib = L
     return _lib
 
@@ -104,6 +108,26 @@ def swconv_set_weights_status(plan, rowptr, colidx, vals):
 def swconv_forward(plan, stream, in_dev_ptr, out_dev_ptr):
     """stream: hipStream_t as int (0 = default); in/out: device addresses as int."""
     _check(lib().swconv_forward(plan, _vp(stream), _vp(in_dev_ptr), _vp(out_dev_ptr)), "swconv_forward")
+
+
+def swconv_backward(plan, stream, in_dev_ptr, dout_dev_ptr, din_dev_ptr, dvals_dev_ptr):
+    """Device addresses as int; din_dev_ptr / dvals_dev_ptr may be 0 (not wanted)."""
+    _check(lib().swconv_backward(plan, _vp(stream), _vp(in_dev_ptr), _vp(dout_dev_ptr), _vp(din_dev_ptr or None),
+                                 _vp(dvals_dev_ptr or None)), "swconv_backward")
+
+
+def swconv_debug_copy_dZ(plan, K):
+    P, T, _, _ = swconv_plan_sizes(plan)
+    dZ = np.empty((P, K, T), dtype=np.float32)
+    _check(lib().swconv_debug_copy_dZ(plan, dZ.ctypes.data_as(_f32p)), "swconv_debug_copy_dZ")
+    return dZ
+
+
+def swconv_debug_copy_dV(plan, C):
+    P, T, _, _ = swconv_plan_sizes(plan)
+    dV = np.empty((P, C, T), dtype=np.float32)
+    _check(lib().swconv_debug_copy_dV(plan, dV.ctypes.data_as(_f32p)), "swconv_debug_copy_dV")
+    return dV
 
 
 def swconv_set_weights_dense(plan, wf):

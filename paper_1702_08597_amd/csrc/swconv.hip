@@ -12,6 +12,7 @@
 #include <numeric>
 #include <vector>
 
+#include "swconv_backward_kernels.hpp"
 #include "swconv_dense_mfma.hpp"
 #include "swconv_kernels.hpp"
 
@@ -85,6 +86,8 @@ struct swconv_plan {
   int n_tau_blocks = 0;
 
   PackedMatrix fw;  // W_F: K rows, panels of C channels (forward)
+  PackedMatrix bt;  // W_F^T: C rows, panels of K channels (backward, Eq. 6 first line); packed on first use
+  bool bt_supported = false, bt_current = false;
 
   // host-built index tables of the transform kernels
   std::vector<TileInfo> tiles;        // Tp
@@ -95,6 +98,8 @@ struct swconv_plan {
   // device
   bool on_device = false, dense_on_device = false, ran_forward = false;
   float *dV = nullptr, *dM = nullptr;
+  float* dD = nullptr;        // backward pass: dL/dI_F, [P][C][Tp]
+  bool ran_backward = false;
   float* d_wdense = nullptr;  // [P][C][Kq]
 };
 
@@ -530,6 +535,65 @@ int copy_padded_to_host(const float* dsrc, float* hdst, size_t rows, int T, int 
   return SWCONV_OK;
 }
 
+// Packs W_F^T (per position: C rows of (k, weight) entries, k ascending) from the packed W_F and
+// allocates the dL/dI_F workspace.  Host work; done by the first backward pass after set_weights.
+int prepare_backward(swconv_plan* pl) {
+  if (!pl->bt_supported) return SWCONV_EUNSUPPORTED;
+  if (pl->bt_current && pl->bt.on_device && pl->dD) return SWCONV_OK;
+  const int P = pl->P, K = pl->g.K, C = pl->g.C;
+  try {
+    const int64_t nnz = pl->fw.nnz;
+    std::vector<int32_t> rp((size_t)P * K + 1), ci((size_t)nnz), trp((size_t)P * C + 1, 0), tci((size_t)nnz);
+    std::vector<float> va((size_t)nnz), tva((size_t)nnz);
+    unpack_matrix(pl->fw, P, rp.data(), ci.data(), va.data());
+    for (int p = 0; p < P; ++p)
+      for (int32_t q = rp[(size_t)p * K]; q < rp[(size_t)(p + 1) * K]; ++q) ++trp[(size_t)p * C + ci[q] + 1];
+    for (size_t i = 0; i < (size_t)P * C; ++i) trp[i + 1] += trp[i];
+    std::vector<int32_t> fill(trp.begin(), trp.end() - 1);
+    for (int p = 0; p < P; ++p)
+      for (int k = 0; k < K; ++k)  // k ascending, so every transposed row gets its columns in ascending order
+        for (int32_t q = rp[(size_t)p * K + k]; q < rp[(size_t)p * K + k + 1]; ++q) {
+          const int32_t dst = fill[(size_t)p * C + ci[q]]++;
+          tci[dst] = k;
+          tva[dst] = va[q];
+        }
+    size_grid(&pl->bt);
+    pack_matrix(&pl->bt, P, pl->n_tau_blocks, trp.data(), tci.data(), tva.data());
+  } catch (const std::bad_alloc&) {
+    pl->bt.packed = false;
+    return SWCONV_ENOMEM;
+  }
+  int rc = upload_packed(&pl->bt);
+  if (rc) return rc;
+  if (!pl->dD) {
+    HIP_TRY(hipMalloc((void**)&pl->dD, pl->g.v_bytes));
+    HIP_TRY(hipMemset(pl->dD, 0, pl->g.v_bytes));
+  }
+  pl->bt_current = true;
+  return SWCONV_OK;
+}
+
+template <int M>
+int launch_backward_transforms(swconv_plan* pl, const LaunchTarget& to, int which, const float* dout,
+                                      float* din) {
+  const Geometry& g = pl->g;
+  if (which == 0) {  // dL/dZ = A dL/dO~ A^T into the M workspace
+    auto kern = output_grad_transform_kernel<M>;
+    static bool attr_set = false;
+    if (!attr_set) {
+      HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
+      attr_set = true;
+    }
+    return launch_kernel(kern, dim3(g.Tp / 64, (g.K + 3) / 4), dim3(256), (size_t)4 * g.out_area * sizeof(float), to,
+                         dout, pl->dM, pl->d_tiles, pl->d_blocks, g);
+  }
+  if (which == 1)  // dL/dI~ = B dL/dI_F B^T, from the dL/dI_F workspace into the V workspace
+    return launch_kernel(input_grad_patch_kernel<M>, dim3(g.Tp / 64, (g.C + 3) / 4), dim3(256), 0, to, pl->dD, pl->dV,
+                         g);
+  return launch_kernel(input_grad_gather_kernel<M>, dim3((g.H * g.W + 255) / 256, g.N * g.C), dim3(256), 0, to,
+                       pl->dV, din, g);
+}
+
 }  // namespace
 
 extern "C" {
@@ -567,6 +631,7 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
     delete pl;
     return SWCONV_EUNSUPPORTED;
   }
+  pl->bt_supported = configure_packed(&pl->bt, C, K);  // the backward pass stages K x 64 panels of dL/dZ
   pl->m = m;
   pl->r = r;
   pl->t = t;
@@ -611,10 +676,11 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
 
 void swconv_plan_destroy(swconv_plan* pl) {
   if (!pl) return;
-  void* bufs[] = {pl->dV, pl->dM, pl->d_wdense, pl->d_tiles, pl->d_blocks};
+  void* bufs[] = {pl->dV, pl->dM, pl->dD, pl->d_wdense, pl->d_tiles, pl->d_blocks};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
   free_packed(&pl->fw);
+  free_packed(&pl->bt);
   delete pl;
 }
 
@@ -623,6 +689,7 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   int rc = validate_csr(pl, rowptr, colidx, vals);
   if (rc) return rc;
   size_grid(&pl->fw);
+  pl->bt_current = false;
   try {
     pack_matrix(&pl->fw, pl->P, pl->n_tau_blocks, rowptr, colidx, vals);
   } catch (const std::bad_alloc&) {
@@ -682,6 +749,46 @@ int swconv_profile_forward(swconv_plan* pl, void* hip_stream, const float* in_de
     if (e) (void)hipEventDestroy(e);
   if (rc) (void)hipGetLastError();
   return rc;
+}
+
+int swconv_backward(swconv_plan* pl, void* hip_stream, const float* in_dev, const float* dout_dev, float* din_dev,
+                    float* dvals_dev) {
+  if (!pl || !in_dev || !dout_dev) return SWCONV_EINVAL;
+  if (!pl->fw.on_device) return SWCONV_ESTATE;
+  if (dvals_dev) return SWCONV_EUNSUPPORTED;  // not built yet
+  if ((int64_t)pl->g.N * pl->g.C > 65535) return SWCONV_EUNSUPPORTED;  // grid.y of the gather
+  int rc = prepare_backward(pl);
+  if (rc) return rc;
+  const LaunchTarget to{(hipStream_t)hip_stream, nullptr, nullptr};
+  const bool m2 = pl->m == 2;
+  // Eq. 5, first line
+  if ((rc = m2 ? launch_backward_transforms<2>(pl, to, 0, dout_dev, nullptr)
+               : launch_backward_transforms<4>(pl, to, 0, dout_dev, nullptr)))
+    return rc;
+  // Eq. 6, first line: dL/dI_F[p] = W_F[p]^T dL/dZ[p]
+  if ((rc = launch_spmm(pl, pl->bt, to, pl->dM, pl->g.m_bytes, pl->dD, pl->g.v_bytes))) return rc;
+  if (din_dev) {
+    // Eq. 6, second and third line
+    for (int which = 1; which <= 2; ++which)
+      if ((rc = m2 ? launch_backward_transforms<2>(pl, to, which, nullptr, din_dev)
+                   : launch_backward_transforms<4>(pl, to, which, nullptr, din_dev)))
+        return rc;
+  }
+  pl->ran_forward = false;  // the V workspace no longer holds I_F
+  pl->ran_backward = true;
+  return SWCONV_OK;
+}
+
+int swconv_debug_copy_dZ(swconv_plan* pl, float* dZ_host) {
+  if (!pl || !dZ_host) return SWCONV_EINVAL;
+  if (!pl->ran_backward) return SWCONV_ESTATE;
+  return copy_padded_to_host(pl->dM, dZ_host, (size_t)pl->P * pl->g.K, pl->g.T, pl->g.Tp);
+}
+
+int swconv_debug_copy_dV(swconv_plan* pl, float* dV_host) {
+  if (!pl || !dV_host) return SWCONV_EINVAL;
+  if (!pl->ran_backward) return SWCONV_ESTATE;
+  return copy_padded_to_host(pl->dD, dV_host, (size_t)pl->P * pl->g.C, pl->g.T, pl->g.Tp);
 }
 
 int swconv_debug_copy_V(swconv_plan* pl, float* V_host) {

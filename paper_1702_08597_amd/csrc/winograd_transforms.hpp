@@ -1,6 +1,7 @@
 // Device-side Winograd transform constants and the two small matrix sandwiches
 //   V = B^T d B   (input transform, step 1 of Section 5 / Eq. 4)
 //   Y = A^T z A   (output transform, step 3)
+//   Z' = A g A^T, D = B f B^T   (their transposes, backward pass: Eq. 5 first line, Eq. 6 second line)
 // for F(2x2,3x3) and F(4x4,3x3).  The paper does not print A and B (Section 3, after Eq. 3,
 // defers to Lavin & Gray); these are the standard minimal-filtering matrices for the points
 // {0,1,-1,inf} and {0,1,-1,2,-2,inf}.
@@ -109,6 +110,94 @@ __device__ __forceinline__ void output_transform(const float (&z)[Wino<M>::t][Wi
   }
 #pragma unroll
   for (int a = 0; a < M; ++a) at_apply<M>(tmp[a], y[a]);
+}
+
+// ---- backward pass (Eq. 5, Eq. 6): the transposed 1-D transforms ----
+
+// z = A g for one column (or row) of an m x m tile of dL/dO~:  z_i = sum_a A^T[a][i] g_a.
+template <int M>
+__device__ __forceinline__ void a_apply(const float (&g)[M], float (&z)[Wino<M>::t]);
+
+template <>
+__device__ __forceinline__ void a_apply<2>(const float (&g)[2], float (&z)[4]) {
+  z[0] = g[0];
+  z[1] = g[0] + g[1];
+  z[2] = g[0] - g[1];
+  z[3] = -g[1];
+}
+
+template <>
+__device__ __forceinline__ void a_apply<4>(const float (&g)[4], float (&z)[6]) {
+  const float e = g[0] + g[2], o = g[1] + g[3];                            // even / odd sums
+  const float e4 = fmaf(4.0f, g[2], g[0]), o4 = fmaf(8.0f, g[3], 2.0f * g[1]);  // g0 + 4 g2, 2 g1 + 8 g3
+  z[0] = g[0];
+  z[1] = e + o;
+  z[2] = e - o;
+  z[3] = e4 + o4;
+  z[4] = e4 - o4;
+  z[5] = g[3];
+}
+
+// d = B f for one column (or row) of a t x t tile of dL/dI_F:  d_a = sum_i B^T[i][a] f_i.
+template <int M>
+__device__ __forceinline__ void b_apply(const float (&f)[Wino<M>::t], float (&d)[Wino<M>::t]);
+
+template <>
+__device__ __forceinline__ void b_apply<2>(const float (&f)[4], float (&d)[4]) {
+  d[0] = f[0];
+  d[1] = f[1] - f[2] + f[3];
+  d[2] = f[1] + f[2] - f[0];
+  d[3] = -f[3];
+}
+
+template <>
+__device__ __forceinline__ void b_apply<4>(const float (&f)[6], float (&d)[6]) {
+  const float s12 = f[1] + f[2], d12 = f[1] - f[2];
+  const float s34 = f[3] + f[4], d34 = f[3] - f[4];
+  d[0] = 4.0f * f[0];
+  d[1] = fmaf(-4.0f, d12, fmaf(-2.0f, d34, 4.0f * f[5]));
+  d[2] = fmaf(-5.0f, f[0], fmaf(-4.0f, s12, -s34));
+  d[3] = fmaf(2.0f, d34, fmaf(-5.0f, f[5], d12));
+  d[4] = f[0] + s12 + s34;
+  d[5] = f[5];
+}
+
+// z = A g A^T  (t x t from m x m): columns first, then rows.
+template <int M>
+__device__ __forceinline__ void output_grad_transform(const float (&g)[M][M],
+                                                      float (&z)[Wino<M>::t][Wino<M>::t]) {
+  constexpr int t = Wino<M>::t;
+  float tmp[t][M];  // A g
+#pragma unroll
+  for (int b = 0; b < M; ++b) {
+    float col[M], res[t];
+#pragma unroll
+    for (int a = 0; a < M; ++a) col[a] = g[a][b];
+    a_apply<M>(col, res);
+#pragma unroll
+    for (int i = 0; i < t; ++i) tmp[i][b] = res[i];
+  }
+#pragma unroll
+  for (int i = 0; i < t; ++i) a_apply<M>(tmp[i], z[i]);
+}
+
+// d = B f B^T  (t x t).
+template <int M>
+__device__ __forceinline__ void input_grad_transform(const float (&f)[Wino<M>::t][Wino<M>::t],
+                                                     float (&d)[Wino<M>::t][Wino<M>::t]) {
+  constexpr int t = Wino<M>::t;
+  float tmp[t][t];  // B f
+#pragma unroll
+  for (int j = 0; j < t; ++j) {
+    float col[t], res[t];
+#pragma unroll
+    for (int i = 0; i < t; ++i) col[i] = f[i][j];
+    b_apply<M>(col, res);
+#pragma unroll
+    for (int a = 0; a < t; ++a) tmp[a][j] = res[a];
+  }
+#pragma unroll
+  for (int a = 0; a < t; ++a) b_apply<M>(tmp[a], d[a]);
 }
 
 }  // namespace swconv
