@@ -73,6 +73,7 @@ struct PackedMatrix {
   std::vector<WorkItem> items;        // in range order
   std::vector<int32_t> wg_begin;      // n_wgs_used + 1 offsets into items, one range per workgroup
   std::vector<RangeHeader> ranges;    // the same, as the kernel reads it
+  std::vector<int32_t> entry_index;   // per stream entry: its index in the caller's CSR arrays, -1 = padding
   uint32_t* d_stream = nullptr;
   Slice* d_slices = nullptr;
   WorkItem* d_items = nullptr;
@@ -99,6 +100,10 @@ struct swconv_plan {
   bool on_device = false, dense_on_device = false, ran_forward = false;
   float *dV = nullptr, *dM = nullptr;
   float* dD = nullptr;        // backward pass: dL/dI_F, [P][C][Tp]
+  float* d_partial = nullptr; // backward pass: [tile blocks][stream entries of W_F] partial dot products
+  size_t partial_floats = 0;
+  int32_t* d_entry_index = nullptr;
+  bool index_current = false;
   bool ran_backward = false;
   float* d_wdense = nullptr;  // [P][C][Kq]
 };
@@ -166,14 +171,15 @@ int launch_output_transform(const swconv_plan* pl, const LaunchTarget& to, float
   return launch_kernel(kern, grid, dim3(256), lds, to, pl->dM, out, pl->d_tiles, pl->d_blocks, pl->g);
 }
 
-// M[p] = A[p] * X[p] for the packed operand `pm`: X has pm.cols rows of Tp tiles per position and
-// x_bytes in all, Y gets pm.rows rows per position.
-template <int NW>
+// Y[p] = A[p] * X[p] for the packed operand `pm`: X has pm.cols rows of Tp tiles per position and
+// x_bytes in all, Y gets pm.rows rows per position.  With `partial` set (sampled mode): Y is read
+// and partial[tile block][stream entry] receives the entry's dot product over the block.
+template <int NW, bool SAMPLED>
 int launch_spmm_t(const swconv_plan* pl, const PackedMatrix& pm, const LaunchTarget& to, const float* X,
-                  uint32_t x_bytes, float* Y, uint32_t y_bytes) {
+                  uint32_t x_bytes, float* Y, uint32_t y_bytes, float* partial) {
   if (pm.n_wgs_used == 0) return SWCONV_OK;
   const size_t lds = (size_t)pm.cols * kTileBlock * sizeof(float) + kSpmmLdsExtra + (size_t)pm.item_cap * sizeof(Slice);
-  auto kern = spmm_kernel<NW>;
+  auto kern = spmm_kernel<NW, SAMPLED>;
   static bool attr_set = false;
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
@@ -181,14 +187,21 @@ int launch_spmm_t(const swconv_plan* pl, const PackedMatrix& pm, const LaunchTar
   }
   return launch_kernel(kern, dim3(pm.n_wgs_used), dim3(NW * 64), lds, to, X, Y, pm.d_stream,
                        (uint32_t)(pm.stream.size() * sizeof(uint32_t)), pm.d_slices, (int)pm.slices.size(),
-                       pm.d_items, pm.d_ranges, pm.n_wgs_used, pm.cols, pm.rows, pl->g.Tp, y_bytes, x_bytes);
+                       pm.d_items, pm.d_ranges, pm.n_wgs_used, pm.cols, pm.rows, pl->g.Tp, y_bytes, x_bytes, partial,
+                       (uint32_t)(pm.stream.size() / 2));
+}
+
+template <bool SAMPLED>
+int launch_spmm_mode(const swconv_plan* pl, const PackedMatrix& pm, const LaunchTarget& to, const float* X,
+                     uint32_t x_bytes, float* Y, uint32_t y_bytes, float* partial) {
+  if (pm.waves == 12) return launch_spmm_t<12, SAMPLED>(pl, pm, to, X, x_bytes, Y, y_bytes, partial);
+  return pm.waves == 16 ? launch_spmm_t<16, SAMPLED>(pl, pm, to, X, x_bytes, Y, y_bytes, partial)
+                        : launch_spmm_t<8, SAMPLED>(pl, pm, to, X, x_bytes, Y, y_bytes, partial);
 }
 
 int launch_spmm(const swconv_plan* pl, const PackedMatrix& pm, const LaunchTarget& to, const float* X,
                 uint32_t x_bytes, float* Y, uint32_t y_bytes) {
-  if (pm.waves == 12) return launch_spmm_t<12>(pl, pm, to, X, x_bytes, Y, y_bytes);
-  return pm.waves == 16 ? launch_spmm_t<16>(pl, pm, to, X, x_bytes, Y, y_bytes)
-                        : launch_spmm_t<8>(pl, pm, to, X, x_bytes, Y, y_bytes);
+  return launch_spmm_mode<false>(pl, pm, to, X, x_bytes, Y, y_bytes, nullptr);
 }
 
 int launch_stage(const swconv_plan* pl, const LaunchTarget& to, int stage, const float* in, float* out) {
@@ -439,6 +452,7 @@ void pack_matrix(PackedMatrix* pm, int P, int ntb, const int32_t* rowptr, const 
   if (cursor * 512 >= ((uint64_t)1 << 32) - 4096) throw std::bad_alloc();
   const uint32_t row_bytes = (uint32_t)kTileBlock * sizeof(float);
   pm->stream.assign((size_t)cursor * 128, 0u);
+  pm->entry_index.assign((size_t)cursor * 64, -1);
   for (size_t s = 0; s < pm->slices.size(); ++s) {
     const Slice& sl = pm->slices[s];
     const int32_t* rp = rowptr + (int64_t)sl.p * R;
@@ -450,6 +464,7 @@ void pack_matrix(PackedMatrix* pm, int P, int ntb, const int32_t* rowptr, const 
         uint32_t* entry = &pm->stream[stream_entry(sl.batch0, r, e)];
         entry[0] = (uint32_t)colidx[q0 + e] * row_bytes;
         std::memcpy(&entry[1], &vals[q0 + e], sizeof(float));
+        pm->entry_index[stream_entry(sl.batch0, r, e) / 2] = q0 + e;
       }
     }
   }
@@ -573,6 +588,26 @@ int prepare_backward(swconv_plan* pl) {
   return SWCONV_OK;
 }
 
+// Device copies the weight gradient needs: the stream-entry -> CSR index map and the partial-sum buffer.
+int prepare_weight_grad(swconv_plan* pl) {
+  const size_t need = (size_t)pl->n_tau_blocks * (pl->fw.stream.size() / 2);
+  if (need * sizeof(float) >= ((size_t)1 << 40)) return SWCONV_EUNSUPPORTED;
+  if (pl->partial_floats < need) {
+    if (pl->d_partial) (void)hipFree(pl->d_partial);
+    pl->d_partial = nullptr;
+    pl->partial_floats = 0;
+    HIP_TRY(hipMalloc((void**)&pl->d_partial, std::max<size_t>(need, 1) * sizeof(float)));
+    pl->partial_floats = need;
+  }
+  if (!pl->index_current) {
+    int rc = upload(&pl->d_entry_index, pl->fw.entry_index);
+    if (rc) return rc;
+    HIP_TRY(hipDeviceSynchronize());
+    pl->index_current = true;
+  }
+  return SWCONV_OK;
+}
+
 template <int M>
 int launch_backward_transforms(swconv_plan* pl, const LaunchTarget& to, int which, const float* dout,
                                       float* din) {
@@ -676,7 +711,7 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
 
 void swconv_plan_destroy(swconv_plan* pl) {
   if (!pl) return;
-  void* bufs[] = {pl->dV, pl->dM, pl->dD, pl->d_wdense, pl->d_tiles, pl->d_blocks};
+  void* bufs[] = {pl->dV, pl->dM, pl->dD, pl->d_partial, pl->d_entry_index, pl->d_wdense, pl->d_tiles, pl->d_blocks};
   for (void* b : bufs)
     if (b) (void)hipFree(b);
   free_packed(&pl->fw);
@@ -690,6 +725,7 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   if (rc) return rc;
   size_grid(&pl->fw);
   pl->bt_current = false;
+  pl->index_current = false;
   try {
     pack_matrix(&pl->fw, pl->P, pl->n_tau_blocks, rowptr, colidx, vals);
   } catch (const std::bad_alloc&) {
@@ -755,16 +791,28 @@ int swconv_backward(swconv_plan* pl, void* hip_stream, const float* in_dev, cons
                     float* dvals_dev) {
   if (!pl || !in_dev || !dout_dev) return SWCONV_EINVAL;
   if (!pl->fw.on_device) return SWCONV_ESTATE;
-  if (dvals_dev) return SWCONV_EUNSUPPORTED;  // not built yet
   if ((int64_t)pl->g.N * pl->g.C > 65535) return SWCONV_EUNSUPPORTED;  // grid.y of the gather
   int rc = prepare_backward(pl);
   if (rc) return rc;
+  if (dvals_dev && (rc = prepare_weight_grad(pl))) return rc;
   const LaunchTarget to{(hipStream_t)hip_stream, nullptr, nullptr};
   const bool m2 = pl->m == 2;
   // Eq. 5, first line
   if ((rc = m2 ? launch_backward_transforms<2>(pl, to, 0, dout_dev, nullptr)
                : launch_backward_transforms<4>(pl, to, 0, dout_dev, nullptr)))
     return rc;
+  if (dvals_dev && pl->fw.nnz > 0) {
+    // Eq. 5, second line: I_F again (step 1 of the forward pass), then per stored entry the dot product of
+    // its dL/dZ row and its I_F row, per tile block, and the sum over the tile blocks
+    if ((rc = launch_stage(pl, to, 0, in_dev, nullptr))) return rc;
+    if ((rc = launch_spmm_mode<true>(pl, pl->fw, to, pl->dV, pl->g.v_bytes, pl->dM, pl->g.m_bytes, pl->d_partial)))
+      return rc;
+    const uint32_t n_entries = (uint32_t)(pl->fw.stream.size() / 2);
+    if ((rc = launch_kernel(weight_grad_reduce_kernel, dim3((n_entries + 255) / 256), dim3(256), 0, to,
+                            (const float*)pl->d_partial, pl->n_tau_blocks, n_entries,
+                            (const int32_t*)pl->d_entry_index, n_entries, dvals_dev)))
+      return rc;
+  }
   // Eq. 6, first line: dL/dI_F[p] = W_F[p]^T dL/dZ[p]
   if ((rc = launch_spmm(pl, pl->bt, to, pl->dM, pl->g.m_bytes, pl->dD, pl->g.v_bytes))) return rc;
   if (din_dev) {

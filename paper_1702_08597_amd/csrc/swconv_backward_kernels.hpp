@@ -153,4 +153,21 @@ __global__ __launch_bounds__(256) void input_grad_gather_kernel(const float* __r
   din[((size_t)nc * g.H + y) * g.W + x] = sum;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Eq. 5, second line, last step: the per-tile-block partial sums of every stream entry (written by
+// the sparse kernel in sampled mode) are added over the tile blocks, in ascending order, and go to
+// the entry's place in the caller's CSR order; padding entries (index -1) are skipped.
+__global__ __launch_bounds__(256) void weight_grad_reduce_kernel(const float* __restrict__ partial, int n_tau_blocks,
+                                                                 uint32_t partial_stride,
+                                                                 const int32_t* __restrict__ entry_index,
+                                                                 uint32_t n_entries, float* __restrict__ dvals) {
+  const uint32_t e = blockIdx.x * 256u + threadIdx.x;
+  if (e >= n_entries) return;
+  const int32_t q = entry_index[e];
+  if (q < 0) return;
+  float sum = 0.0f;
+  for (int tb = 0; tb < n_tau_blocks; ++tb) sum += partial[(size_t)tb * partial_stride + e];
+  dvals[q] = sum;
+}
+
 }  // namespace swconv

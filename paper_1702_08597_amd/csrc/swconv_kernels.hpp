@@ -316,22 +316,35 @@ __device__ __forceinline__ void quarter_fma(Acc4& acc, uint32_t bw, const f32x4_
 #undef SWCONV_QFMA
 }
 
-// Steps G*kStepGroup .. +kStepGroup-1 of the batch held in (boff, bw): the four panel reads
-// are issued back to back, the FMAs follow as the data arrives.
+// The four panel reads of steps G*kStepGroup .. +kStepGroup-1 of the batch whose row offsets are in
+// boff, issued back to back.
+struct Group4 {
+  f32x4_t x0, x1, x2, x3;
+};
+template <int G>
+__device__ __forceinline__ Group4 quarter_reads(const float* panel, uint32_t lane_sub, uint32_t boff) {
+  constexpr int I0 = G * kStepGroup;
+  static_assert(kStepGroup == 4, "four steps per group");
+  const char* base = reinterpret_cast<const char*>(panel);
+  Group4 g;
+  g.x0 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 0>(boff) + lane_sub));
+  g.x1 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 1>(boff) + lane_sub));
+  g.x2 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 2>(boff) + lane_sub));
+  g.x3 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 3>(boff) + lane_sub));
+  return g;
+}
+
+// Steps G*kStepGroup .. +kStepGroup-1 of the batch held in (boff, bw): the reads, then the FMAs as
+// the data arrives.
 template <int G>
 __device__ __forceinline__ void quarter_group(const float* panel, uint32_t lane_sub, uint32_t boff, uint32_t bw,
                                               Acc4& acc) {
   constexpr int I0 = G * kStepGroup;
-  static_assert(kStepGroup == 4, "four steps per group");
-  const char* base = reinterpret_cast<const char*>(panel);
-  const f32x4_t x0 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 0>(boff) + lane_sub));
-  const f32x4_t x1 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 1>(boff) + lane_sub));
-  const f32x4_t x2 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 2>(boff) + lane_sub));
-  const f32x4_t x3 = *reinterpret_cast<const f32x4_t*>(base + (quarter_bcast<I0 + 3>(boff) + lane_sub));
-  quarter_fma<I0 + 0, true>(acc, bw, x0);
-  quarter_fma<I0 + 1, false>(acc, bw, x1);
-  quarter_fma<I0 + 2, false>(acc, bw, x2);
-  quarter_fma<I0 + 3, false>(acc, bw, x3);
+  const Group4 g = quarter_reads<G>(panel, lane_sub, boff);
+  quarter_fma<I0 + 0, true>(acc, bw, g.x0);
+  quarter_fma<I0 + 1, false>(acc, bw, g.x1);
+  quarter_fma<I0 + 2, false>(acc, bw, g.x2);
+  quarter_fma<I0 + 3, false>(acc, bw, g.x3);
 }
 
 // The first `steps` (a positive multiple of kStepGroup, wave-uniform) steps of one batch.
@@ -343,11 +356,61 @@ __device__ __forceinline__ void quarter_batch(const float* panel, uint32_t lane_
   if (steps > 3 * kStepGroup) quarter_group<3>(panel, lane_sub, b.x, b.y, acc);
 }
 
-template <int NWAVES>
+// ---- sampled mode (backward pass, Eq. 5 second line): dL/dW_F at the stored entries ----
+// The same walk over the packed W_F, but instead of accumulating w * x into the row, every stored
+// entry (k, c) gets the dot product of dL/dZ[p][k][.] with the panel row of c over the 64 tiles of
+// the block: the lane multiplies its four tiles, the 16 lanes of the quarter are summed with four
+// DPP exchanges, and lane i of the quarter keeps the sum of step i, so that after a batch every
+// lane holds the partial sum of "its" stream entry and the wave stores 256 contiguous bytes.
+
+// Sum over the 16 lanes of a quarter; every lane gets the total.
+__device__ __forceinline__ float quarter_sum(float d) {
+  d += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, d), 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
+  d += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, d), 0x4E, 0xf, 0xf, true));   // quad_perm [2,3,0,1]
+  d += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, d), 0x141, 0xf, 0xf, true));  // row_half_mirror
+  d += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, d), 0x140, 0xf, 0xf, true));  // row_mirror
+  return d;
+}
+
+template <int G>
+__device__ __forceinline__ void sampled_group(const float* panel, uint32_t lane_sub, uint32_t boff, const f32x4_t& z,
+                                              int lane_in_quarter, float& res) {
+  constexpr int I0 = G * kStepGroup;
+  const Group4 g = quarter_reads<G>(panel, lane_sub, boff);
+  const f32x4_t* x[4] = {&g.x0, &g.x1, &g.x2, &g.x3};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const f32x4_t& v = *x[i];
+    float d = z[0] * v[0];
+    d = fmaf(z[1], v[1], d);
+    d = fmaf(z[2], v[2], d);
+    d = fmaf(z[3], v[3], d);
+    d = quarter_sum(d);
+    res = lane_in_quarter == I0 + i ? d : res;
+  }
+}
+
+// The first `steps` steps of one batch; returns, in lane (q, i), the partial sum of row q, step i
+// (0 for steps that were not run).
+__device__ __forceinline__ float sampled_batch(const float* panel, uint32_t lane_sub, const u32x2_t& b, int steps,
+                                               const f32x4_t& z, int lane_in_quarter) {
+  float res = 0.0f;
+  sampled_group<0>(panel, lane_sub, b.x, z, lane_in_quarter, res);
+  if (steps > 1 * kStepGroup) sampled_group<1>(panel, lane_sub, b.x, z, lane_in_quarter, res);
+  if (steps > 2 * kStepGroup) sampled_group<2>(panel, lane_sub, b.x, z, lane_in_quarter, res);
+  if (steps > 3 * kStepGroup) sampled_group<3>(panel, lane_sub, b.x, z, lane_in_quarter, res);
+  return res;
+}
+
+// SAMPLED = false: Mbuf[p] = A[p] * V[p] (forward step 2; backward Eq. 6 first line on the packed
+// transpose).  SAMPLED = true: Mbuf is read (dL/dZ), and partial[tau_block][stream entry] gets the
+// entry's dot product over that tile block (Eq. 5 second line; `partial_stride` entries per block).
+template <int NWAVES, bool SAMPLED>
 __global__ __launch_bounds__(NWAVES * 64, NWAVES == 12 ? 6 : 4) void spmm_kernel(
     const float* __restrict__ V, float* __restrict__ Mbuf, const uint32_t* __restrict__ stream, uint32_t stream_bytes,
     const Slice* __restrict__ slices, int n_slices, const WorkItem* __restrict__ items,
-    const RangeHeader* __restrict__ ranges, int n_wgs, int C, int K, int Tp, uint32_t m_bytes, uint32_t v_bytes) {
+    const RangeHeader* __restrict__ ranges, int n_wgs, int C, int K, int Tp, uint32_t m_bytes, uint32_t v_bytes,
+    float* __restrict__ partial, uint32_t partial_stride) {
   constexpr int NT = NWAVES * 64;
   constexpr int TB = kTileBlock;
   typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
@@ -408,6 +471,14 @@ __global__ __launch_bounds__(NWAVES * 64, NWAVES == 12 ? 6 : 4) void spmm_kernel
   // memory round trip.
   Cur cur;
   u32x2_t b0 = {0u, 0u}, b1 = {0u, 0u};
+  // sampled mode: the lane's four tiles of the dL/dZ row of its quarter (zeros for a padding row)
+  f32x4_t z_cur = {0.0f, 0.0f, 0.0f, 0.0f};
+  auto row_offset = [&](int p, int tau0, int k) -> uint32_t {  // quarters of padding rows are parked beyond the buffer
+    return k >= 0 ? (((uint32_t)p * K + (uint32_t)k) * Tp + tau0) * 4u + lane_sub : 0xfffffff0u;
+  };
+  auto load_z = [&](int p, int tau0, int k) -> f32x4_t {
+    return __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(mr, (int)row_offset(p, tau0, k), 0, 0));
+  };
   auto start_item = [&](const WorkItem& w) {
     const uint32_t soff = ((uint32_t)w.p * C * Tp + (uint32_t)w.tau_block * TB) * 4u;
 #pragma unroll
@@ -423,6 +494,7 @@ __global__ __launch_bounds__(NWAVES * 64, NWAVES == 12 ? 6 : 4) void spmm_kernel
     cur.k = quarter_k(sl.k[0], sl.k[1], sl.k[2], sl.k[3]);
     b0 = load_batch(cur.base);
     b1 = load_batch(cur.base + 512u);
+    if constexpr (SAMPLED) z_cur = load_z(w.p, w.tau_block * TB, cur.k);
   };
 
   WorkItem it = hdr.first;
@@ -430,6 +502,9 @@ __global__ __launch_bounds__(NWAVES * 64, NWAVES == 12 ? 6 : 4) void spmm_kernel
   for (int item = hdr.item_begin;; ++item) {
     const int tau0 = it.tau_block * TB;
     const int n_item_slices = it.slice_end - it.slice_begin;
+    // sampled mode: this tile block's row of the partial-sum buffer, one float per stream entry
+    const __amdgpu_buffer_rsrc_t pr =
+        make_rsrc(SAMPLED ? partial + (size_t)it.tau_block * partial_stride : nullptr, SAMPLED ? partial_stride * 4u : 0u);
     const bool has_next = item + 1 < hdr.item_end;
     const WorkItem it_next = items[has_next ? item + 1 : item];
     if (item != hdr.item_begin) __syncthreads();  // every wave is done with the previous panel and descriptors
@@ -464,24 +539,38 @@ __global__ __launch_bounds__(NWAVES * 64, NWAVES == 12 ? 6 : 4) void spmm_kernel
         nxt.len = __builtin_amdgcn_readfirstlane((int)d_head.y);
         nxt.k = quarter_k((int)d_k.x, (int)d_k.y, (int)d_k.z, (int)d_k.w);
         const int batches = (cur.len + kBatchSteps - 1) / kBatchSteps;
+        f32x4_t z_next = {0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (SAMPLED) z_next = load_z(it.p, tau0, more ? nxt.k : -1);
         for (int j = 0, remaining = cur.len; j < batches; j += 2, remaining -= 2 * kBatchSteps) {
-          quarter_batch(panel, lane_sub, b0, remaining, acc);
+          if constexpr (SAMPLED) {
+            const float r0 = sampled_batch(panel, lane_sub, b0, remaining, z_cur, lane & 15);
+            buffer_store_f32<SWCONV_AUX_M>(pr, lane * 4u, cur.base / 2u + (uint32_t)j * 256u, r0);
+          } else {
+            quarter_batch(panel, lane_sub, b0, remaining, acc);
+          }
           b0 = load_batch(j + 2 < batches ? cur.base + (uint32_t)(j + 2) * 512u : nxt.base);
-          if (j + 1 < batches) quarter_batch(panel, lane_sub, b1, remaining - kBatchSteps, acc);
+          if (j + 1 < batches) {
+            if constexpr (SAMPLED) {
+              const float r1 = sampled_batch(panel, lane_sub, b1, remaining - kBatchSteps, z_cur, lane & 15);
+              buffer_store_f32<SWCONV_AUX_M>(pr, lane * 4u, cur.base / 2u + (uint32_t)(j + 1) * 256u, r1);
+            } else {
+              quarter_batch(panel, lane_sub, b1, remaining - kBatchSteps, acc);
+            }
+          }
           b1 = load_batch(j + 3 < batches ? cur.base + (uint32_t)(j + 3) * 512u : nxt.base + 512u);
         }
         if (batches == 0) {  // an all-empty slice consumed nothing: fetch the next slice's batches here
           b0 = load_batch(nxt.base);
           b1 = load_batch(nxt.base + 512u);
         }
-        // quarters of padding rows are parked beyond the buffer
-        const uint32_t moff =
-            cur.k >= 0 ? (((uint32_t)it.p * K + (uint32_t)cur.k) * Tp + tau0) * 4u + lane_sub : 0xfffffff0u;
-        const u32x4v_t result = {__float_as_uint(acc.a0), __float_as_uint(acc.a1), __float_as_uint(acc.a2),
-                                 __float_as_uint(acc.a3)};
-        __builtin_amdgcn_raw_buffer_store_b128(result, mr, (int)moff, 0, SWCONV_AUX_M);
+        if constexpr (!SAMPLED) {
+          const u32x4v_t result = {__float_as_uint(acc.a0), __float_as_uint(acc.a1), __float_as_uint(acc.a2),
+                                   __float_as_uint(acc.a3)};
+          __builtin_amdgcn_raw_buffer_store_b128(result, mr, (int)row_offset(it.p, tau0, cur.k), 0, SWCONV_AUX_M);
+        }
         if (!more) break;
         cur = nxt;
+        z_cur = z_next;
       }
     }
     if (!has_next) break;

@@ -119,4 +119,4 @@ def test_unsupported_K_is_refused():
         sw.swconv_plan_destroy(plan)
 
 
-WANT_DVALS = False  # the weight-gradient kernel is not built yet
+WANT_DVALS = True
