@@ -6,7 +6,7 @@ output transform) over one batch of seeded synthetic input that is already resid
 Metric: effective TFLOP/s = FLOPs a dense direct convolution would execute / time (the paper's
 Fig. 2 definition).  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--density D] [--rotate R]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--density D] [--rotate R] [--backward]
 """
 import argparse
 import json
@@ -40,6 +40,94 @@ def stage_models(cfg, nnz):
     ]
 
 
+def backward_stage_models(cfg, nnz, padded_entries):
+    """Algorithmic bytes and flops of the seven backward kernels for one launch (launch order)."""
+    N, C, H, W, K = cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"]
+    P, T, Ho, Wo = cfg["P"], cfg["T"], cfg["Ho"], cfg["Wo"]
+    ntb = (T + 63) // 64
+    return [
+        dict(bytes=4 * (N * K * Ho * Wo + P * K * T), flops=0),                      # dZ = A dO A^T
+        dict(bytes=4 * (N * C * H * W + P * C * T), flops=0),                        # I_F again
+        dict(bytes=4 * (P * C * T + P * K * T) + 8 * nnz + 4 * ntb * nnz, flops=2 * nnz * T),  # sampled products
+        dict(bytes=4 * ntb * nnz + 8 * nnz, flops=0),                                # reduction to CSR order
+        dict(bytes=4 * (P * K * T + P * C * T) + 8 * nnz, flops=2 * nnz * T),        # dI_F = W_F^T dZ
+        dict(bytes=8 * P * C * T, flops=0),                                          # patches = B dI_F B^T
+        dict(bytes=4 * (P * C * T + N * C * H * W), flops=0),                        # gather
+    ]
+
+
+def run_backward(args, sw, synth, torch, np, plan, cfg, name, x, xd, rp, ci, va, nnz, flops_direct, sp):
+    """The backward pass (Section 3, Eq. 5 and Eq. 6): dL/dI and dL/dW_F (stored entries) from dL/dO."""
+    dev = xd.device
+    sw.swconv_set_weights(plan, rp, ci, va)
+    G = np.random.default_rng(cfg["seed"] + 5).standard_normal((cfg["N"], cfg["K"], cfg["Ho"], cfg["Wo"])).astype(
+        np.float32)
+    gd = torch.from_numpy(G).to(dev)
+    din = torch.empty_like(xd)
+    dvals = torch.empty((max(1, nnz),), dtype=torch.float32, device=dev)
+    a = (plan, sp, xd.data_ptr(), gd.data_ptr(), din.data_ptr(), dvals.data_ptr())
+    for _ in range(args.warmup):
+        sw.swconv_backward(*a)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        sw.swconv_backward(*a)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    # the two gradients each cost what the forward pass costs as a direct convolution
+    flops = 2 * flops_direct
+    result = {
+        "metric": "effective TFLOP/s of the backward pass (2 x direct-conv FLOPs / time), 1 MI355X",
+        "value": round(flops / (elapsed / args.steps) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": name, "N": cfg["N"], "C": cfg["C"], "H": cfg["H"], "W": cfg["W"], "K": cfg["K"],
+                   "winograd": "F(%dx%d,3x3)" % (cfg["m"], cfg["m"]), "pad": cfg["pad"],
+                   "density": (nnz / float(cfg["P"] * cfg["K"] * cfg["C"])), "nnz": nnz,
+                   "path": "backward (dL/dI and dL/dW_F)"},
+    }
+    stage_ms = sw.swconv_profile_backward(*a, args.steps)
+    st = sw.swconv_plan_weight_stats(plan)
+    models = backward_stage_models(cfg, nnz, st["padded_nnz"])
+    stages = []
+    for nm, ms, mdl in zip(sw.BACKWARD_STAGES, stage_ms.tolist(), models):
+        gbs = mdl["bytes"] / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        tfl = mdl["flops"] / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+        stages.append({"kernel": nm, "ms": round(ms, 6), "alg_bytes": mdl["bytes"], "alg_flops": mdl["flops"],
+                       "GBps": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4), "TFLOPs": round(tfl, 3),
+                       "fp32_frac": round(tfl / FP32_VECTOR_TFLOPS, 4)})
+    dom = max(range(len(stages)), key=lambda i: stage_ms[i])
+    d, mdl = stages[dom], models[dom]
+    if mdl["bytes"] / (HBM_PEAK_GBS * 1e9) >= mdl["flops"] / (FP32_VECTOR_TFLOPS * 1e12):
+        roof = {"bound": "hbm", "achieved": d["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": d["hbm_frac"]}
+    else:
+        roof = {"bound": "alu", "achieved": d["TFLOPs"], "peak": FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+                "frac": d["fp32_frac"]}
+    roof.update({"kernel": d["kernel"], "avg_ms": d["ms"], "traffic": None})
+    result["roofline"] = roof
+    result["stages"] = stages
+    if not args.no_cpu_baseline:
+        import oracle
+
+        times = []
+        t_start = time.perf_counter()
+        while True:
+            t0 = time.perf_counter()
+            oracle.backward_f32(x, rp, ci, va, G, cfg["K"], cfg["m"], cfg["r"], cfg["pad"])
+            times.append(time.perf_counter() - t0)
+            if len(times) >= 5 or time.perf_counter() - t_start > 20.0:
+                break
+        t_med = sorted(times)[len(times) // 2]
+        result["cpu_baseline"] = {"value": round(flops / t_med / 1e12, 5), "unit": "TFLOP/s",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": "full workload (%d images), median of %d runs, fp32 instantiation"
+                                            % (cfg["N"], len(times)),
+                                  "seconds": round(t_med, 4)}
+    sw.swconv_plan_destroy(plan)
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,6 +136,8 @@ def main():
     ap.add_argument("--workload", default=None)
     ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--dense", action="store_true", help="time the 0%%-sparsity MFMA comparison path instead")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the backward pass of the layer (dL/dI and dL/dW_F from dL/dO) instead of the forward pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=1, metavar="R",
                     help="cold-cache regime: step i runs on the i %% R-th of R independent sets of plan, workspaces, "
@@ -91,6 +181,9 @@ def main():
     out = torch.empty((cfg["N"], cfg["K"], cfg["Ho"], cfg["Wo"]), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
     sp, xp, op = stream.cuda_stream, xd.data_ptr(), out.data_ptr()
+    if args.backward:
+        run_backward(args, sw, synth, torch, np, plan, cfg, name, x, xd, rp, ci, va, nnz, flops_direct, sp)
+        return
     if args.dense:
         wf = synth.dense_weights(cfg["P"], cfg["K"], cfg["C"], cfg["seed"] + 2000)
         sw.swconv_set_weights_dense(plan, wf)

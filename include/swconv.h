@@ -133,6 +133,17 @@ int swconv_forward_dense(swconv_plan* plan, void* hip_stream, const float* in_de
 int swconv_backward(swconv_plan* plan, void* hip_stream, const float* in_dev, const float* dout_dev, float* din_dev,
                     float* dvals_dev);
 
+/*
+ * Measurement helper for the backward pass: `iters` passes with every kernel launched with its own
+ * pair of HIP events (as swconv_profile_forward); mean milliseconds per kernel, in launch order:
+ *   stage_ms  HOST, 7 floats: dL/dZ transform, input transform (I_F again), sampled products,
+ *             reduction to CSR order, transposed sparse product, patch transform, gather;
+ *             0 for kernels the call does not run (din_dev or dvals_dev NULL).
+ * Blocks the host.  Errors as for swconv_backward; EINVAL for iters < 1.
+ */
+int swconv_profile_backward(swconv_plan* plan, void* hip_stream, const float* in_dev, const float* dout_dev,
+                            float* din_dev, float* dvals_dev, int iters, float* stage_ms);
+
 /* Test hooks: intermediates of the last backward pass, canonical layouts.
  *   dZ_host  HOST, [P][K][T] (dL/dZ)      dV_host  HOST, [P][C][T] (dL/dI_F)
  * Errors: ESTATE when no backward pass has run; EHIP. */

@@ -17,7 +17,7 @@ EXPORTS = [
     "swconv_forward", "swconv_set_weights_dense", "swconv_forward_dense", "swconv_profile_forward",
     "swconv_debug_copy_V", "swconv_debug_copy_M", "swconv_debug_export_weights", "swconv_plan_sizes",
     "swconv_plan_weight_stats", "swconv_debug_check_schedule",
-    "swconv_backward", "swconv_debug_copy_dZ", "swconv_debug_copy_dV",
+    "swconv_backward", "swconv_debug_copy_dZ", "swconv_debug_copy_dV", "swconv_profile_backward",
 ]
 
 _lib = None
@@ -58,6 +58,7 @@ def lib():
                                                ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int64)]
         L.swconv_debug_check_schedule.argtypes = [_vp]
         L.swconv_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
+        L.swconv_profile_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int, _f32p]
         L.swconv_debug_copy_dZ.argtypes = [_vp, _f32p]
         L.swconv_debug_copy_dV.argtypes = [_vp, _f32p]
         _lib = L
@@ -114,6 +115,20 @@ def swconv_backward(plan, stream, in_dev_ptr, dout_dev_ptr, din_dev_ptr, dvals_d
     """Device addresses as int; din_dev_ptr / dvals_dev_ptr may be 0 (not wanted)."""
     _check(lib().swconv_backward(plan, _vp(stream), _vp(in_dev_ptr), _vp(dout_dev_ptr), _vp(din_dev_ptr or None),
                                  _vp(dvals_dev_ptr or None)), "swconv_backward")
+
+
+BACKWARD_STAGES = ("output_grad_transform_kernel", "input_transform_kernel", "spmm_kernel<sampled>",
+                   "weight_grad_reduce_kernel", "spmm_kernel<transposed>", "input_grad_patch_kernel",
+                   "input_grad_gather_kernel")
+
+
+def swconv_profile_backward(plan, stream, in_dev_ptr, dout_dev_ptr, din_dev_ptr, dvals_dev_ptr, iters):
+    """-> numpy float32[7]: mean milliseconds of each backward kernel, in launch order (BACKWARD_STAGES)."""
+    ms = np.zeros(7, dtype=np.float32)
+    _check(lib().swconv_profile_backward(plan, _vp(stream), _vp(in_dev_ptr), _vp(dout_dev_ptr),
+                                         _vp(din_dev_ptr or None), _vp(dvals_dev_ptr or None), int(iters),
+                                         ms.ctypes.data_as(_f32p)), "swconv_profile_backward")
+    return ms
 
 
 def swconv_debug_copy_dZ(plan, K):

@@ -629,6 +629,55 @@ int launch_backward_transforms(swconv_plan* pl, const LaunchTarget& to, int whic
                        pl->dV, din, g);
 }
 
+// The kernels of the backward pass, in launch order.
+//   0  dL/dZ = A dL/dO~ A^T                      (Eq. 5, first line)      -> M workspace
+//   1  I_F = B^T I~ B again (forward step 1)                              -> V workspace   } only for
+//   2  per stored entry and tile block: <dL/dZ row, I_F row>              -> partial sums  } dL/dW_F
+//   3  sum over the tile blocks, CSR order        (Eq. 5, second line)    -> dvals         }
+//   4  dL/dI_F[p] = W_F[p]^T dL/dZ[p]             (Eq. 6, first line)     -> dL/dI_F workspace
+//   5  dL/dI~ = B dL/dI_F B^T                     (Eq. 6, second line)    -> V workspace   } only for
+//   6  every pixel gathers its patch entries      (Eq. 6, third line)     -> din           } dL/dI
+constexpr int kBackwardStages = 7;
+
+bool backward_stage_runs(const swconv_plan* pl, int stage, const float* din, const float* dvals) {
+  if (stage >= 1 && stage <= 3) return dvals != nullptr && pl->fw.nnz > 0;
+  if (stage >= 5) return din != nullptr;
+  return true;
+}
+
+int backward_ready(swconv_plan* pl, const float* in_dev, const float* dout_dev, const float* dvals_dev) {
+  if (!pl || !in_dev || !dout_dev) return SWCONV_EINVAL;
+  if (!pl->fw.on_device) return SWCONV_ESTATE;
+  if ((int64_t)pl->g.N * pl->g.C > 65535) return SWCONV_EUNSUPPORTED;  // grid.y of the gather
+  int rc = prepare_backward(pl);
+  if (rc) return rc;
+  return dvals_dev ? prepare_weight_grad(pl) : SWCONV_OK;
+}
+
+int launch_backward_stage(swconv_plan* pl, const LaunchTarget& to, int stage, const float* in_dev,
+                          const float* dout_dev, float* din_dev, float* dvals_dev) {
+  if (!backward_stage_runs(pl, stage, din_dev, dvals_dev)) return SWCONV_OK;
+  const bool m2 = pl->m == 2;
+  switch (stage) {
+    case 0:
+      return m2 ? launch_backward_transforms<2>(pl, to, 0, dout_dev, nullptr)
+                : launch_backward_transforms<4>(pl, to, 0, dout_dev, nullptr);
+    case 1: return launch_stage(pl, to, 0, in_dev, nullptr);
+    case 2:
+      return launch_spmm_mode<true>(pl, pl->fw, to, pl->dV, pl->g.v_bytes, pl->dM, pl->g.m_bytes, pl->d_partial);
+    case 3: {
+      const uint32_t n_entries = (uint32_t)(pl->fw.stream.size() / 2);
+      return launch_kernel(weight_grad_reduce_kernel, dim3((n_entries + 255) / 256), dim3(256), 0, to,
+                           (const float*)pl->d_partial, pl->n_tau_blocks, n_entries,
+                           (const int32_t*)pl->d_entry_index, n_entries, dvals_dev);
+    }
+    case 4: return launch_spmm(pl, pl->bt, to, pl->dM, pl->g.m_bytes, pl->dD, pl->g.v_bytes);
+    default:
+      return m2 ? launch_backward_transforms<2>(pl, to, stage - 4, nullptr, din_dev)
+                : launch_backward_transforms<4>(pl, to, stage - 4, nullptr, din_dev);
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -789,42 +838,52 @@ int swconv_profile_forward(swconv_plan* pl, void* hip_stream, const float* in_de
 
 int swconv_backward(swconv_plan* pl, void* hip_stream, const float* in_dev, const float* dout_dev, float* din_dev,
                     float* dvals_dev) {
-  if (!pl || !in_dev || !dout_dev) return SWCONV_EINVAL;
-  if (!pl->fw.on_device) return SWCONV_ESTATE;
-  if ((int64_t)pl->g.N * pl->g.C > 65535) return SWCONV_EUNSUPPORTED;  // grid.y of the gather
-  int rc = prepare_backward(pl);
+  int rc = backward_ready(pl, in_dev, dout_dev, dvals_dev);
   if (rc) return rc;
-  if (dvals_dev && (rc = prepare_weight_grad(pl))) return rc;
-  const LaunchTarget to{(hipStream_t)hip_stream, nullptr, nullptr};
-  const bool m2 = pl->m == 2;
-  // Eq. 5, first line
-  if ((rc = m2 ? launch_backward_transforms<2>(pl, to, 0, dout_dev, nullptr)
-               : launch_backward_transforms<4>(pl, to, 0, dout_dev, nullptr)))
-    return rc;
-  if (dvals_dev && pl->fw.nnz > 0) {
-    // Eq. 5, second line: I_F again (step 1 of the forward pass), then per stored entry the dot product of
-    // its dL/dZ row and its I_F row, per tile block, and the sum over the tile blocks
-    if ((rc = launch_stage(pl, to, 0, in_dev, nullptr))) return rc;
-    if ((rc = launch_spmm_mode<true>(pl, pl->fw, to, pl->dV, pl->g.v_bytes, pl->dM, pl->g.m_bytes, pl->d_partial)))
+  for (int stage = 0; stage < kBackwardStages; ++stage)
+    if ((rc = launch_backward_stage(pl, LaunchTarget{(hipStream_t)hip_stream, nullptr, nullptr}, stage, in_dev,
+                                    dout_dev, din_dev, dvals_dev)))
       return rc;
-    const uint32_t n_entries = (uint32_t)(pl->fw.stream.size() / 2);
-    if ((rc = launch_kernel(weight_grad_reduce_kernel, dim3((n_entries + 255) / 256), dim3(256), 0, to,
-                            (const float*)pl->d_partial, pl->n_tau_blocks, n_entries,
-                            (const int32_t*)pl->d_entry_index, n_entries, dvals_dev)))
-      return rc;
-  }
-  // Eq. 6, first line: dL/dI_F[p] = W_F[p]^T dL/dZ[p]
-  if ((rc = launch_spmm(pl, pl->bt, to, pl->dM, pl->g.m_bytes, pl->dD, pl->g.v_bytes))) return rc;
-  if (din_dev) {
-    // Eq. 6, second and third line
-    for (int which = 1; which <= 2; ++which)
-      if ((rc = m2 ? launch_backward_transforms<2>(pl, to, which, nullptr, din_dev)
-                   : launch_backward_transforms<4>(pl, to, which, nullptr, din_dev)))
-        return rc;
-  }
   pl->ran_forward = false;  // the V workspace no longer holds I_F
   pl->ran_backward = true;
   return SWCONV_OK;
+}
+
+int swconv_profile_backward(swconv_plan* pl, void* hip_stream, const float* in_dev, const float* dout_dev,
+                            float* din_dev, float* dvals_dev, int iters, float* stage_ms) {
+  if (!stage_ms || iters < 1) return SWCONV_EINVAL;
+  int rc = backward_ready(pl, in_dev, dout_dev, dvals_dev);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // one (start, stop) pair per kernel launch; the events take the kernel's own time stamps
+  std::vector<hipEvent_t> ev((size_t)iters * kBackwardStages * 2, nullptr);
+  for (auto& e : ev)
+    if (hipEventCreate(&e) != hipSuccess) rc = SWCONV_EHIP;
+  for (int it = 0; it < iters && !rc; ++it)
+    for (int stage = 0; stage < kBackwardStages && !rc; ++stage) {
+      hipEvent_t* e = &ev[((size_t)it * kBackwardStages + stage) * 2];
+      rc = launch_backward_stage(pl, LaunchTarget{st, e[0], e[1]}, stage, in_dev, dout_dev, din_dev, dvals_dev);
+    }
+  if (hipStreamSynchronize(st) != hipSuccess) rc = rc ? rc : SWCONV_EHIP;
+  if (!rc) {
+    for (int stage = 0; stage < kBackwardStages; ++stage) {
+      double sum = 0;
+      if (backward_stage_runs(pl, stage, din_dev, dvals_dev))
+        for (int it = 0; it < iters && !rc; ++it) {
+          hipEvent_t* e = &ev[((size_t)it * kBackwardStages + stage) * 2];
+          float ms = 0;
+          if (hipEventElapsedTime(&ms, e[0], e[1]) != hipSuccess) rc = SWCONV_EHIP;
+          sum += ms;
+        }
+      stage_ms[stage] = (float)(sum / iters);
+    }
+    pl->ran_forward = false;
+    pl->ran_backward = true;
+  }
+  for (auto& e : ev)
+    if (e) (void)hipEventDestroy(e);
+  if (rc) (void)hipGetLastError();
+  return rc;
 }
 
 int swconv_debug_copy_dZ(swconv_plan* pl, float* dZ_host) {

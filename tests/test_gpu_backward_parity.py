@@ -104,6 +104,27 @@ def test_full_size_configs(name):
           stages=(cfg["N"] <= 32), want_dvals=WANT_DVALS)
 
 
+def test_profile_backward_reports_seven_kernels_and_skips_unwanted_ones():
+    N, C, H, W, K, m = 4, 16, 13, 13, 12, 4
+    x = synth.activations(N, C, H, W, 1)
+    rp, ci, va = synth.bernoulli_weights(36, K, C, 0.3, 2)
+    plan = sw.swconv_plan_create(N, C, H, W, K, m, 3, 1)
+    try:
+        sw.swconv_set_weights(plan, rp, ci, va)
+        xd = torch.from_numpy(x).cuda()
+        gd = torch.ones((N, K, 13, 13), device="cuda")
+        din = torch.empty_like(xd)
+        dv = torch.empty((len(va),), device="cuda")
+        ms = sw.swconv_profile_backward(plan, 0, xd.data_ptr(), gd.data_ptr(), din.data_ptr(), dv.data_ptr(), 3)
+        assert ms.shape == (7,) and np.all(ms > 0) and np.all(ms < 50)
+        ms = sw.swconv_profile_backward(plan, 0, xd.data_ptr(), gd.data_ptr(), din.data_ptr(), 0, 3)
+        assert np.all(ms[1:4] == 0) and ms[0] > 0 and np.all(ms[4:] > 0)
+        ms = sw.swconv_profile_backward(plan, 0, xd.data_ptr(), gd.data_ptr(), 0, dv.data_ptr(), 3)
+        assert np.all(ms[5:] == 0) and np.all(ms[:5] > 0)
+    finally:
+        sw.swconv_plan_destroy(plan)
+
+
 def test_unsupported_K_is_refused():
     plan = sw.swconv_plan_create(1, 4, 6, 6, 700, 2, 3, 1)
     try:
