@@ -42,8 +42,17 @@ __global__ __launch_bounds__(256) void output_grad_transform_kernel(const float*
       // loads past the part's end return 0 (descriptor), so the padded tail of the run is zero
       const __amdgpu_buffer_rsrc_t src = make_rsrc(dout + ((size_t)b.n * g.K + k) * plane + b.out_elem0,
                                                    (uint32_t)b.out_span * 4u);
-      float* dst = my + b.out_off;
-      for (int e0 = 0; e0 < b.out_span; e0 += 64) dst[e0 + lane] = buffer_load_f32(src, lane * 4u, e0 * 4u);
+      float* dst = my + b.out_off + lane;
+      constexpr int EL = 4;  // loads per lane in flight
+      for (int e0 = 0; e0 < b.out_span; e0 += 64 * EL) {
+        float buf[EL];
+#pragma unroll
+        for (int u = 0; u < EL; ++u)
+          if (e0 + u * 64 < b.out_span) buf[u] = buffer_load_f32(src, (lane + u * 64) * 4u, e0 * 4u);
+#pragma unroll
+        for (int u = 0; u < EL; ++u)
+          if (e0 + u * 64 < b.out_span) dst[e0 + u * 64] = buf[u];
+      }
     }
   }
   __syncthreads();
