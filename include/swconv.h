@@ -120,7 +120,10 @@ int swconv_forward_dense(swconv_plan* plan, void* hip_stream, const float* in_de
  *   dL/dW_F(:,:,p) = dL/dZ(:,:,p) I_F(:,:,p)^T,  at the stored entries of the pruned W_F only
  *   dL/dI_F(:,:,p) = W_F(:,:,p)^T dL/dZ(:,:,p),  dL/dI~ = B dL/dI_F B^T,  dL/dI = overlap-add through phi
  * enqueued on `hip_stream`.
- *   in_dev     DEVICE, N x C x H x W, the input of the forward pass (I_F is recomputed from it)
+ *   in_dev     DEVICE, N x C x H x W, the input of the forward pass (I_F is recomputed from it); or NULL:
+ *              I_F is taken from the plan's workspace, where the last swconv_forward on this plan left it
+ *              (ESTATE if a backward pass or no forward pass came after swconv_set_weights; only needed
+ *              for dL/dW_F)
  *   dout_dev   DEVICE, N x K x Ho x Wo, dL/dO
  *   din_dev    DEVICE, N x C x H x W or NULL: dL/dI, every element overwritten
  *   dvals_dev  DEVICE, nnz floats or NULL: dL/dW_F at the stored entries, in the order of the CSR

@@ -639,15 +639,17 @@ int launch_backward_transforms(swconv_plan* pl, const LaunchTarget& to, int whic
 //   6  every pixel gathers its patch entries      (Eq. 6, third line)     -> din           } dL/dI
 constexpr int kBackwardStages = 7;
 
-bool backward_stage_runs(const swconv_plan* pl, int stage, const float* din, const float* dvals) {
+bool backward_stage_runs(const swconv_plan* pl, int stage, const float* in, const float* din, const float* dvals) {
+  if (stage == 1 && !in) return false;  // I_F of the last forward pass is still in the V workspace
   if (stage >= 1 && stage <= 3) return dvals != nullptr && pl->fw.nnz > 0;
   if (stage >= 5) return din != nullptr;
   return true;
 }
 
 int backward_ready(swconv_plan* pl, const float* in_dev, const float* dout_dev, const float* dvals_dev) {
-  if (!pl || !in_dev || !dout_dev) return SWCONV_EINVAL;
+  if (!pl || !dout_dev) return SWCONV_EINVAL;
   if (!pl->fw.on_device) return SWCONV_ESTATE;
+  if (!in_dev && dvals_dev && !pl->ran_forward) return SWCONV_ESTATE;  // no I_F to reuse
   if ((int64_t)pl->g.N * pl->g.C > 65535) return SWCONV_EUNSUPPORTED;  // grid.y of the gather
   int rc = prepare_backward(pl);
   if (rc) return rc;
@@ -656,7 +658,7 @@ int backward_ready(swconv_plan* pl, const float* in_dev, const float* dout_dev, 
 
 int launch_backward_stage(swconv_plan* pl, const LaunchTarget& to, int stage, const float* in_dev,
                           const float* dout_dev, float* din_dev, float* dvals_dev) {
-  if (!backward_stage_runs(pl, stage, din_dev, dvals_dev)) return SWCONV_OK;
+  if (!backward_stage_runs(pl, stage, in_dev, din_dev, dvals_dev)) return SWCONV_OK;
   const bool m2 = pl->m == 2;
   switch (stage) {
     case 0:
@@ -868,7 +870,7 @@ int swconv_profile_backward(swconv_plan* pl, void* hip_stream, const float* in_d
   if (!rc) {
     for (int stage = 0; stage < kBackwardStages; ++stage) {
       double sum = 0;
-      if (backward_stage_runs(pl, stage, din_dev, dvals_dev))
+      if (backward_stage_runs(pl, stage, in_dev, din_dev, dvals_dev))
         for (int it = 0; it < iters && !rc; ++it) {
           hipEvent_t* e = &ev[((size_t)it * kBackwardStages + stage) * 2];
           float ms = 0;

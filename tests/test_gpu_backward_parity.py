@@ -104,6 +104,34 @@ def test_full_size_configs(name):
           stages=(cfg["N"] <= 32), want_dvals=WANT_DVALS)
 
 
+def test_backward_can_reuse_the_forward_pass_transform():
+    N, C, H, W, K, m = 5, 20, 13, 13, 18, 4
+    rng = np.random.default_rng(9100)
+    x = synth.activations(N, C, H, W, 9101)
+    rp, ci, va = synth.bernoulli_weights(36, K, C, 0.3, 9102)
+    G = rng.standard_normal((N, K, 13, 13)).astype(np.float32)
+    din64, dvals64, _, _ = oracle.backward_f64(x, rp, ci, va, G, K, m, want_ZV=False)
+    plan = sw.swconv_plan_create(N, C, H, W, K, m, 3, 1)
+    try:
+        sw.swconv_set_weights(plan, rp, ci, va)
+        xd, gd = torch.from_numpy(x).cuda(), torch.from_numpy(G).cuda()
+        out = torch.empty((N, K, 13, 13), device="cuda")
+        din = torch.full((N, C, H, W), float("nan"), device="cuda")
+        dv = torch.full((len(va),), float("nan"), device="cuda")
+        with pytest.raises(sw.SwconvError) as e:     # nothing to reuse yet
+            sw.swconv_backward(plan, 0, 0, gd.data_ptr(), din.data_ptr(), dv.data_ptr())
+        assert e.value.status == sw.SWCONV_ESTATE
+        sw.swconv_forward(plan, 0, xd.data_ptr(), out.data_ptr())
+        sw.swconv_backward(plan, 0, 0, gd.data_ptr(), din.data_ptr(), dv.data_ptr())
+        torch.cuda.synchronize()
+        assert relerr(din.cpu().numpy(), din64) <= RTOL[m]
+        assert relerr(dv.cpu().numpy(), dvals64) <= RTOL[m]
+        with pytest.raises(sw.SwconvError):          # the backward pass used the workspace
+            sw.swconv_backward(plan, 0, 0, gd.data_ptr(), din.data_ptr(), dv.data_ptr())
+    finally:
+        sw.swconv_plan_destroy(plan)
+
+
 def test_profile_backward_reports_seven_kernels_and_skips_unwanted_ones():
     N, C, H, W, K, m = 4, 16, 13, 13, 12, 4
     x = synth.activations(N, C, H, W, 1)
