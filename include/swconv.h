@@ -131,7 +131,7 @@ int swconv_forward_dense(swconv_plan* plan, void* hip_stream, const float* in_de
  * The first call after swconv_set_weights also packs the transposed weights on the host and blocks.
  * Overwrites the plan's workspaces (swconv_debug_copy_V / _M then see backward data).
  * Errors: EINVAL, ESTATE (no weights), EUNSUPPORTED (K > 638: the panels of dL/dZ do not fit LDS; or
- * N*C > 65535), ENOMEM, EHIP.
+ * N*C*(H+m)*(W+m) >= 2^31), ENOMEM, EHIP.
  */
 int swconv_backward(swconv_plan* plan, void* hip_stream, const float* in_dev, const float* dout_dev, float* din_dev,
                     float* dvals_dev);

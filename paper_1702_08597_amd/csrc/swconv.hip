@@ -625,8 +625,10 @@ int launch_backward_transforms(swconv_plan* pl, const LaunchTarget& to, int whic
   if (which == 1)  // dL/dI~ = B dL/dI_F B^T, from the dL/dI_F workspace into the V workspace
     return launch_kernel(input_grad_patch_kernel<M>, dim3(g.Tp / 64, (g.C + 3) / 4), dim3(256), 0, to, pl->dD, pl->dV,
                          g);
-  return launch_kernel(input_grad_gather_kernel<M>, dim3((g.H * g.W + 255) / 256, g.N * g.C), dim3(256), 0, to,
-                       pl->dV, din, g);
+  const int cells = ((g.H - 1 + g.pad) / M + 1) * ((g.W - 1 + g.pad) / M + 1);
+  const int64_t threads = (int64_t)g.N * g.C * cells;
+  return launch_kernel(input_grad_gather_kernel<M>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, to, pl->dV,
+                       din, g);
 }
 
 // The kernels of the backward pass, in launch order.
@@ -650,7 +652,7 @@ int backward_ready(swconv_plan* pl, const float* in_dev, const float* dout_dev, 
   if (!pl || !dout_dev) return SWCONV_EINVAL;
   if (!pl->fw.on_device) return SWCONV_ESTATE;
   if (!in_dev && dvals_dev && !pl->ran_forward) return SWCONV_ESTATE;  // no I_F to reuse
-  if ((int64_t)pl->g.N * pl->g.C > 65535) return SWCONV_EUNSUPPORTED;  // grid.y of the gather
+  if ((int64_t)pl->g.N * pl->g.C * (pl->g.H + pl->m) * (pl->g.W + pl->m) >= ((int64_t)1 << 31)) return SWCONV_EUNSUPPORTED;  // 32-bit cell index of the gather
   int rc = prepare_backward(pl);
   if (rc) return rc;
   return dvals_dev ? prepare_weight_grad(pl) : SWCONV_OK;

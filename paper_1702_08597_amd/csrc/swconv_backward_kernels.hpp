@@ -127,39 +127,62 @@ __global__ __launch_bounds__(256) void input_grad_patch_kernel(const float* __re
 }
 
 // ---------------------------------------------------------------------------------------------
-// Eq. 6, third line, as a gather: a thread owns one input pixel (n, c, y, x) and adds the entries
-// of the at most 2 x 2 patches that phi maps to it, tiles in ascending order, so every pixel is
-// written once and the sum has a fixed order.  (t - m = r - 1 < m for the supported F(m, 3), so a
-// pixel lies in at most two tiles per dimension.)  Grid: x = pixel chunks of a plane, y = (n, c).
+// Eq. 6, third line, as a gather.  The input plane is cut into m x m cells aligned with the tile
+// stride: cell (qy, qx) holds the pixels y = qy*m - pad + ry, x = qx*m - pad + rx.  Every pixel of a
+// cell receives from the same at most 2 x 2 tiles (qy - dy, qx - dx), dy, dx in {0, 1}, the patch
+// entry (ry + m*dy, rx + m*dx) where that lies inside the t x t patch (t - m = r - 1 <= m).  A
+// thread owns one cell of one (n, c) plane and lanes run over consecutive cells, i.e. consecutive
+// tiles, so every patch load of a wave is a contiguous run of one position plane and each patch
+// entry is read exactly once; each pixel is written once, its sum taken in ascending tile order.
+// Threads run over all cells of all (n, c) planes.
 template <int M>
 __global__ __launch_bounds__(256) void input_grad_gather_kernel(const float* __restrict__ patches,
                                                                 float* __restrict__ din, const Geometry g) {
   constexpr int t = Wino<M>::t;
-  static_assert(t - M < M || M == 2, "two tiles per dimension");
-  const int e = blockIdx.x * 256 + threadIdx.x;
-  if (e >= g.H * g.W) return;
-  const int nc = blockIdx.y, n = nc / g.C, c = nc - n * g.C;
-  const int y = e / g.W, x = e - y * g.W;
-  const int qy = (y + g.pad) / M, ry = (y + g.pad) - qy * M;
-  const int qx = (x + g.pad) / M, rx = (x + g.pad) - qx * M;
+  static_assert(t - M <= M, "a pixel lies in at most two tiles per dimension");
+  const int cells_y = (g.H - 1 + g.pad) / M + 1, cells_x = (g.W - 1 + g.pad) / M + 1;
+  const int cells = cells_y * cells_x;
+  const uint32_t idx = blockIdx.x * 256u + threadIdx.x;  // (n, c) plane major, cells of a plane consecutive
+  if (idx >= (uint32_t)g.N * g.C * cells) return;
+  const int nc = idx / cells, cell = idx - nc * cells;
+  const int n = nc / g.C, c = nc - n * g.C;
+  const int qy = cell / cells_x, qx = cell - qy * cells_x;
   const __amdgpu_buffer_rsrc_t src = make_rsrc(patches, g.v_bytes);
   const uint32_t pstride = (uint32_t)g.C * (uint32_t)g.Tp;  // floats between positions
-  float sum = 0.0f;
-  // tiles ty = qy - dy with patch row a = ry + M * dy < t, ascending ty first
-  constexpr int kBack = (t - 1) / M;  // how many tiles back a pixel can reach: 1 for F(4,3) and F(2,3)
+  float acc[M][M];
 #pragma unroll
-  for (int dy = kBack; dy >= 0; --dy) {
-    const int ty = qy - dy, a = ry + M * dy;
-    if (ty < 0 || ty >= g.th || a >= t) continue;
+  for (int ry = 0; ry < M; ++ry)
 #pragma unroll
-    for (int dx = kBack; dx >= 0; --dx) {
-      const int tx = qx - dx, b = rx + M * dx;
-      if (tx < 0 || tx >= g.tw || b >= t) continue;
-      const uint32_t tau = (uint32_t)(n * g.th + ty) * g.tw + tx;
-      sum += buffer_load_f32(src, (((uint32_t)(a * t + b) * pstride) + (uint32_t)c * g.Tp + tau) * 4u, 0);
+    for (int rx = 0; rx < M; ++rx) acc[ry][rx] = 0.0f;
+  // tiles in ascending order: (qy-1, qx-1), (qy-1, qx), (qy, qx-1), (qy, qx)
+#pragma unroll
+  for (int dy = 1; dy >= 0; --dy) {
+    const int ty = qy - dy;
+#pragma unroll
+    for (int dx = 1; dx >= 0; --dx) {
+      const int tx = qx - dx;
+      if (ty < 0 || ty >= g.th || tx < 0 || tx >= g.tw) continue;
+      const uint32_t base = ((uint32_t)c * g.Tp + (uint32_t)(n * g.th + ty) * g.tw + tx) * 4u;
+#pragma unroll
+      for (int ry = 0; ry < M; ++ry)
+#pragma unroll
+        for (int rx = 0; rx < M; ++rx) {
+          const int a = ry + M * dy, b = rx + M * dx;  // compile-time after unrolling
+          if (a < t && b < t) acc[ry][rx] += buffer_load_f32(src, base + (uint32_t)(a * t + b) * pstride * 4u, 0);
+        }
     }
   }
-  din[((size_t)nc * g.H + y) * g.W + x] = sum;
+  float* plane = din + (size_t)nc * g.H * g.W;
+#pragma unroll
+  for (int ry = 0; ry < M; ++ry) {
+    const int y = qy * M - g.pad + ry;
+    if (y < 0 || y >= g.H) continue;
+#pragma unroll
+    for (int rx = 0; rx < M; ++rx) {
+      const int x = qx * M - g.pad + rx;
+      if (x >= 0 && x < g.W) plane[y * g.W + x] = acc[ry][rx];
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
