@@ -52,6 +52,9 @@ def _load():
         lib.oracle_forward_f32.argtypes = ints8 + [f32p, i32p, i32p, f32p, f32p, f32p, f32p]
         lib.oracle_backward_f64.argtypes = ints8 + [f64p, i32p, i32p, f64p, f64p, f64p, f64p, f64p, f64p]
         lib.oracle_backward_f32.argtypes = ints8 + [f32p, i32p, i32p, f32p, f32p, f32p, f32p, f32p, f32p]
+        for fn, fp, ct in ((lib.oracle_prune_step_f32, f32p, ctypes.c_float), (lib.oracle_prune_step_f64, f64p, ctypes.c_double)):
+            fn.argtypes = [ctypes.c_int64, i32p, i32p, fp, fp, ct, ct, ct, ct, fp, i32p, i32p, fp]
+            fn.restype = ctypes.c_int64
         lib.oracle_direct_conv_f64.argtypes = [ctypes.c_int] * 7 + [f64p, f64p, f64p]
         lib.oracle_wf_from_spatial_f64.argtypes = [ctypes.c_int] * 4 + [f64p, f64p]
         lib.oracle_winograd_matrices.argtypes = [ctypes.c_int] * 2 + [f64p, f64p, f64p]
@@ -137,6 +140,27 @@ def backward_f32(inp, rowptr, colidx, vals, dout, K, m, r=3, pad=1, want_ZV=Fals
     """The same loops in float: the timed CPU baseline of the backward pass."""
     return _backward(_load().oracle_backward_f32, np.float32, ctypes.c_float, inp, rowptr, colidx, vals, dout, K, m,
                      r, pad, want_ZV)
+
+
+def prune_step(rowptr, colidx, vals, grad, eta, lam, eps=1e-4, beta=0.1, dtype=np.float32):
+    """Eq. 9 + Eq. 8 on the stored entries: -> (updated values in the old pattern, (rowptr, colidx, vals) of the
+    kept entries).  dtype float32 takes every rounding and the keep/drop decision in float, as the GPU kernel does."""
+    dt = np.dtype(dtype)
+    ct = ctypes.c_float if dt == np.float32 else ctypes.c_double
+    fn = _load().oracle_prune_step_f32 if dt == np.float32 else _load().oracle_prune_step_f64
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=dt)
+    grad = np.ascontiguousarray(grad, dtype=dt)
+    assert vals.shape == grad.shape == colidx.shape == (int(rowptr[-1]),)
+    updated = np.empty_like(vals)
+    rp = np.empty_like(rowptr)
+    ci = np.empty_like(colidx)
+    va = np.empty_like(vals)
+    kept = fn(len(rowptr) - 1, _ptr(rowptr, ctypes.c_int32), _ptr(colidx, ctypes.c_int32), _ptr(vals, ct),
+              _ptr(grad, ct), ct(eta), ct(lam), ct(eps), ct(beta), _ptr(updated, ct), _ptr(rp, ctypes.c_int32),
+              _ptr(ci, ctypes.c_int32), _ptr(va, ct))
+    return updated, (rp, ci[:kept].copy(), va[:kept].copy())
 
 
 def direct_conv_f64(inp, w, pad):

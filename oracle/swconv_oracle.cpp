@@ -22,6 +22,10 @@
 //     the stored entries of the pruned W_F), dL/dI_F(:,:,i,j) = W_F(:,:,i,j)^T
 //     dL/dZ(:,:,i,j), dL/dI~ = B dL/dI_F B^T and the overlap-add through phi.
 //
+//   * Section 4.2, Eq. 8 and Eq. 9 - one pruning step on the stored entries of W_F:
+//     w <- T_{eps,beta}(w - eta (dL/dw + lambda sign w)), T(w) = 0 if |w| (|dL/dw| + beta) < eps,
+//     followed by dropping the zeroed entries from the CSR pattern.
+//
 // Every pin that ties these functions to the paper lives in tests/ (brute
 // force on tiny inputs, zero weights, linearity, single non-zero closed form,
 // the overlapped-tiling example of Section 3, permutation invariances).
@@ -42,6 +46,7 @@
 // float (the timed CPU baseline).  OpenMP over independent outer iterations
 // only; no blocking, fusion or reordering.
 
+#include <cmath>
 #include <cstdint>
 #include <cstring>
 #include <vector>
@@ -365,9 +370,54 @@ int winograd_layer_backward(int N, int C, int H, int W, int K, int m, int r, int
   return 0;
 }
 
+// Eq. 9 with the L1 penalty of Eq. 7 (its subgradient lambda * sign(w), sign(0) = 0), then the
+// thresholding function of Eq. 8 applied to the updated value with the magnitude of the same
+// gradient dL/dw(theta^(k)).  One rounding per operation in `real`: the sum g + lambda*sign(w),
+// one fused multiply-add for w - eta * (.), the sum |g| + beta, the product with |w'|.
+//   updated [nnz]: w' where kept, 0 where thresholded (the pattern of the input)
+//   rowptr_out [rows+1], colidx_out / vals_out: the kept entries only (capacity nnz); returns their count
+template <typename real>
+int64_t prune_step(int64_t rows, const int32_t* rowptr, const int32_t* colidx, const real* vals, const real* grad,
+                   real eta, real lambda, real eps, real beta, real* updated, int32_t* rowptr_out,
+                   int32_t* colidx_out, real* vals_out) {
+  int64_t kept = 0;
+  rowptr_out[0] = 0;
+  for (int64_t row = 0; row < rows; ++row) {
+    for (int32_t q = rowptr[row]; q < rowptr[row + 1]; ++q) {
+      const real w = vals[q], g = grad[q];
+      const real sgn = w > 0 ? (real)1 : (w < 0 ? (real)-1 : (real)0);
+      const real step = g + lambda * sgn;
+      const real wn = std::fma(-eta, step, w);
+      const bool drop = std::fabs(wn) * (std::fabs(g) + beta) < eps;
+      if (updated) updated[q] = drop ? (real)0 : wn;
+      if (!drop) {
+        colidx_out[kept] = colidx[q];
+        vals_out[kept] = wn;
+        ++kept;
+      }
+    }
+    rowptr_out[row + 1] = (int32_t)kept;
+  }
+  return kept;
+}
+
 }  // namespace
 
 extern "C" {
+
+int64_t oracle_prune_step_f32(int64_t rows, const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                              const float* grad, float eta, float lambda, float eps, float beta, float* updated,
+                              int32_t* rowptr_out, int32_t* colidx_out, float* vals_out) {
+  return prune_step<float>(rows, rowptr, colidx, vals, grad, eta, lambda, eps, beta, updated, rowptr_out, colidx_out,
+                           vals_out);
+}
+int64_t oracle_prune_step_f64(int64_t rows, const int32_t* rowptr, const int32_t* colidx, const double* vals,
+                              const double* grad, double eta, double lambda, double eps, double beta, double* updated,
+                              int32_t* rowptr_out, int32_t* colidx_out, double* vals_out) {
+  return prune_step<double>(rows, rowptr, colidx, vals, grad, eta, lambda, eps, beta, updated, rowptr_out, colidx_out,
+                            vals_out);
+}
+
 
 // Eq. 5 and Eq. 6 in double / float.  dZ, dV, dvals, din may each be NULL.
 int oracle_backward_f64(int N, int C, int H, int W, int K, int m, int r, int pad, const double* in,
