@@ -137,6 +137,34 @@ int swconv_backward(swconv_plan* plan, void* hip_stream, const float* in_dev, co
                     float* dvals_dev);
 
 /*
+ * One pruning step on the stored entries of W_F (Section 4.2): the SGD step of Eq. 9 on L + lambda |w|_1
+ * (Eq. 7; the subgradient of |w| at 0 is taken as 0), then the thresholding function of Eq. 8,
+ *     w' = w - eta (dL/dw + lambda sign w),   T(w') = 0 if |w'| (|dL/dw| + beta) < eps, else w'
+ * with dL/dw the gradient the step was taken with (e.g. the dvals of swconv_backward), and the per-position
+ * CSR of the entries that survive.  The paper recommends eps = 1e-4, beta = 0.1.  fp32, one rounding per
+ * operation (sum, fused multiply-add, sum, product), so the keep/drop decision is reproducible.
+ * Enqueued on `hip_stream` (three small kernels); independent of any plan.
+ *   rows            P*K, the CSR rows
+ *   rowptr_dev      DEVICE, rows + 1 entries; colidx_dev, vals_dev, grad_dev DEVICE, nnz entries, CSR order
+ *   updated_dev     DEVICE, nnz floats: T(w') in the OLD pattern (0 where dropped); must not alias vals_dev
+ *                   (the last kernel takes the decisions again from vals_dev)
+ *   rowptr_out_dev  DEVICE, rows + 1 entries; colidx_out_dev, vals_out_dev DEVICE, capacity nnz: the new CSR;
+ *                   its entry count is rowptr_out_dev[rows]
+ * Errors: EINVAL (null pointers, rows < 1, a negative or NaN hyper-parameter), EHIP.
+ */
+int swconv_prune_step(int64_t rows, const int32_t* rowptr_dev, const int32_t* colidx_dev, const float* vals_dev,
+                      const float* grad_dev, float eta, float lambda, float eps, float beta, void* hip_stream,
+                      float* updated_dev, int32_t* rowptr_out_dev, int32_t* colidx_out_dev, float* vals_out_dev);
+
+/*
+ * swconv_set_weights for CSR arrays that live on the device (e.g. the output of swconv_prune_step): waits
+ * for `hip_stream`, copies the arrays to the host (the re-packing is host code) and proceeds as
+ * swconv_set_weights.  Blocks the host.  Errors as for swconv_set_weights, EHIP for a failed copy.
+ */
+int swconv_set_weights_device(swconv_plan* plan, void* hip_stream, const int32_t* rowptr_dev,
+                              const int32_t* colidx_dev, const float* vals_dev);
+
+/*
  * Measurement helper for the backward pass: `iters` passes with every kernel launched with its own
  * pair of HIP events (as swconv_profile_forward); mean milliseconds per kernel, in launch order:
  *   stage_ms  HOST, 7 floats: dL/dZ transform, input transform (I_F again), sampled products,

@@ -33,7 +33,7 @@ def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(
-            ["g++", "-O2", "-std=c++17", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC]
+            ["g++", "-O2", "-ffp-contract=off", "-std=c++17", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC]
         )
         os.replace(tmp, _LIB)
     return _LIB

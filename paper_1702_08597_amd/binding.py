@@ -18,6 +18,7 @@ EXPORTS = [
     "swconv_debug_copy_V", "swconv_debug_copy_M", "swconv_debug_export_weights", "swconv_plan_sizes",
     "swconv_plan_weight_stats", "swconv_debug_check_schedule",
     "swconv_backward", "swconv_debug_copy_dZ", "swconv_debug_copy_dV", "swconv_profile_backward",
+    "swconv_prune_step", "swconv_set_weights_device",
 ]
 
 _lib = None
@@ -59,6 +60,8 @@ def lib():
         L.swconv_debug_check_schedule.argtypes = [_vp]
         L.swconv_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
         L.swconv_profile_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int, _f32p]
+        L.swconv_prune_step.argtypes = [ctypes.c_int64, _vp, _vp, _vp, _vp] + [ctypes.c_float] * 4 + [_vp] * 5
+        L.swconv_set_weights_device.argtypes = [_vp] * 5
         L.swconv_debug_copy_dZ.argtypes = [_vp, _f32p]
         L.swconv_debug_copy_dV.argtypes = [_vp, _f32p]
         _lib = L
@@ -115,6 +118,19 @@ def swconv_backward(plan, stream, in_dev_ptr, dout_dev_ptr, din_dev_ptr, dvals_d
     """Device addresses as int; din_dev_ptr / dvals_dev_ptr may be 0 (not wanted)."""
     _check(lib().swconv_backward(plan, _vp(stream), _vp(in_dev_ptr), _vp(dout_dev_ptr), _vp(din_dev_ptr or None),
                                  _vp(dvals_dev_ptr or None)), "swconv_backward")
+
+
+def swconv_prune_step(rows, rowptr_dev, colidx_dev, vals_dev, grad_dev, eta, lam, eps, beta, stream, updated_dev,
+                      rowptr_out_dev, colidx_out_dev, vals_out_dev):
+    """Device addresses as int."""
+    _check(lib().swconv_prune_step(int(rows), _vp(rowptr_dev), _vp(colidx_dev), _vp(vals_dev), _vp(grad_dev),
+                                   float(eta), float(lam), float(eps), float(beta), _vp(stream), _vp(updated_dev),
+                                   _vp(rowptr_out_dev), _vp(colidx_out_dev), _vp(vals_out_dev)), "swconv_prune_step")
+
+
+def swconv_set_weights_device(plan, stream, rowptr_dev, colidx_dev, vals_dev):
+    _check(lib().swconv_set_weights_device(plan, _vp(stream), _vp(rowptr_dev), _vp(colidx_dev), _vp(vals_dev)),
+           "swconv_set_weights_device")
 
 
 BACKWARD_STAGES = ("output_grad_transform_kernel", "input_transform_kernel", "spmm_kernel<sampled>",

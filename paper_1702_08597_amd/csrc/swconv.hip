@@ -15,6 +15,7 @@
 #include "swconv_backward_kernels.hpp"
 #include "swconv_dense_mfma.hpp"
 #include "swconv_kernels.hpp"
+#include "swconv_prune_kernels.hpp"
 
 using namespace swconv;
 
@@ -900,6 +901,51 @@ int swconv_debug_copy_dV(swconv_plan* pl, float* dV_host) {
   if (!pl || !dV_host) return SWCONV_EINVAL;
   if (!pl->ran_backward) return SWCONV_ESTATE;
   return copy_padded_to_host(pl->dD, dV_host, (size_t)pl->P * pl->g.C, pl->g.T, pl->g.Tp);
+}
+
+int swconv_prune_step(int64_t rows, const int32_t* rowptr_dev, const int32_t* colidx_dev, const float* vals_dev,
+                      const float* grad_dev, float eta, float lambda, float eps, float beta, void* hip_stream,
+                      float* updated_dev, int32_t* rowptr_out_dev, int32_t* colidx_out_dev, float* vals_out_dev) {
+  if (rows < 1 || rows >= ((int64_t)1 << 31) - 256 || !rowptr_dev || !updated_dev || !rowptr_out_dev ||
+      !colidx_out_dev || !vals_out_dev)
+    return SWCONV_EINVAL;
+  if (!(eta >= 0.0f) || !(lambda >= 0.0f) || !(eps >= 0.0f) || !(beta >= 0.0f)) return SWCONV_EINVAL;
+  const LaunchTarget to{(hipStream_t)hip_stream, nullptr, nullptr};
+  const dim3 grid((unsigned)((rows + 255) / 256));
+  int rc;
+  if ((rc = launch_kernel(prune_update_kernel, grid, dim3(256), 0, to, rows, rowptr_dev, vals_dev, grad_dev, eta, lambda,
+                          eps, beta, updated_dev, rowptr_out_dev)))
+    return rc;
+  if ((rc = launch_kernel(prune_scan_kernel, dim3(1), dim3(1024), 0, to, rows, rowptr_out_dev))) return rc;
+  return launch_kernel(prune_compact_kernel, grid, dim3(256), 0, to, rows, rowptr_dev, colidx_dev, vals_dev, grad_dev,
+                       eta, lambda, eps, beta, (const int32_t*)rowptr_out_dev, colidx_out_dev, vals_out_dev);
+}
+
+int swconv_set_weights_device(swconv_plan* pl, void* hip_stream, const int32_t* rowptr_dev, const int32_t* colidx_dev,
+                              const float* vals_dev) {
+  if (!pl || !rowptr_dev) return SWCONV_EINVAL;
+  const size_t rows = (size_t)pl->P * pl->g.K;
+  try {
+    std::vector<int32_t> rp(rows + 1);
+    if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess ||
+        hipMemcpy(rp.data(), rowptr_dev, rp.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess) {
+      (void)hipGetLastError();
+      return SWCONV_EHIP;
+    }
+    const int64_t nnz = rp[rows];
+    if (rp[0] != 0 || nnz < 0 || nnz > (int64_t)rows * pl->g.C) return SWCONV_EINVAL;
+    if (nnz > 0 && (!colidx_dev || !vals_dev)) return SWCONV_EINVAL;
+    std::vector<int32_t> ci((size_t)nnz);
+    std::vector<float> va((size_t)nnz);
+    if (nnz > 0 && (hipMemcpy(ci.data(), colidx_dev, ci.size() * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess ||
+                    hipMemcpy(va.data(), vals_dev, va.size() * sizeof(float), hipMemcpyDeviceToHost) != hipSuccess)) {
+      (void)hipGetLastError();
+      return SWCONV_EHIP;
+    }
+    return swconv_set_weights(pl, rp.data(), ci.data(), va.data());
+  } catch (const std::bad_alloc&) {
+    return SWCONV_ENOMEM;
+  }
 }
 
 int swconv_debug_copy_V(swconv_plan* pl, float* V_host) {

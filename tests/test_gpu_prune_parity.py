@@ -1,0 +1,78 @@
+"""GPU parity of the pruning step (Eq. 8, Eq. 9) against the oracle's float instantiation: the keep/drop
+decision is taken in fp32 on both sides with one rounding per operation, so everything is bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1702_08597_amd import binding as sw
+from paper_1702_08597_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_prune(rp, ci, va, g, eta, lam, eps, beta):
+    d = lambda a: torch.from_numpy(a).cuda()
+    rpd, cid, vad, gd = d(rp), d(ci), d(va), d(g)
+    n = max(1, len(va))
+    upd = torch.full((n,), float("nan"), device="cuda")
+    rp2 = torch.full((len(rp),), -7, dtype=torch.int32, device="cuda")
+    ci2 = torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    va2 = torch.full((n,), float("nan"), device="cuda")
+    sw.swconv_prune_step(len(rp) - 1, rpd.data_ptr(), cid.data_ptr(), vad.data_ptr(), gd.data_ptr(), eta, lam, eps,
+                         beta, torch.cuda.current_stream().cuda_stream, upd.data_ptr(), rp2.data_ptr(), ci2.data_ptr(),
+                         va2.data_ptr())
+    torch.cuda.synchronize()
+    rp2_host = rp2.cpu().numpy()
+    k = int(rp2_host[-1])
+    return upd.cpu().numpy()[:len(va)], rp2_host, ci2.cpu().numpy()[:k], va2.cpu().numpy()[:k], (rp2, ci2, va2)
+
+
+@pytest.mark.parametrize("P,K,C,density,seed", [(36, 384, 256, 0.1, 1), (16, 7, 5, 0.5, 2), (36, 2100, 3, 0.7, 3),
+                                                (4, 3, 9, 0.0, 4), (36, 40, 600, 1.0, 5)])
+def test_prune_step_bit_exact(P, K, C, density, seed):
+    rng = np.random.default_rng(seed)
+    rp, ci, va = synth.bernoulli_weights(P, K, C, density, seed + 10, sigma=2e-3)
+    g = (rng.standard_normal(len(va)) * 0.05).astype(np.float32)
+    g[::5] = 0.0
+    eta, lam, eps, beta = 0.01, 1e-3, 1e-4, 0.1
+    upd_o, (rp_o, ci_o, va_o) = oracle.prune_step(rp, ci, va, g, eta, lam, eps, beta, np.float32)
+    upd, rp2, ci2, va2, _ = gpu_prune(rp, ci, va, g, eta, lam, eps, beta)
+    if len(va):
+        assert 0 < rp_o[-1] < len(va) or density in (0.0,)
+    np.testing.assert_array_equal(upd.view(np.uint32), upd_o.view(np.uint32))
+    np.testing.assert_array_equal(rp2, rp_o)
+    np.testing.assert_array_equal(ci2, ci_o)
+    np.testing.assert_array_equal(va2.view(np.uint32), va_o.view(np.uint32))
+
+
+def test_backward_prune_set_weights_forward_round():
+    """One training-style round on the device: forward, backward, pruning step, new weights, forward."""
+    cfg = dict(N=4, C=32, H=13, W=13, K=24, m=4, pad=1)
+    N, C, H, W, K, m, pad = (cfg[k] for k in ("N", "C", "H", "W", "K", "m", "pad"))
+    x = synth.activations(N, C, H, W, 50)
+    rp, ci, va = synth.bernoulli_weights(36, K, C, 0.3, 51, sigma=2e-3)
+    G = np.random.default_rng(52).standard_normal((N, K, 13, 13)).astype(np.float32)
+    plan = sw.swconv_plan_create(N, C, H, W, K, m, 3, pad)
+    try:
+        sw.swconv_set_weights(plan, rp, ci, va)
+        xd, gd = torch.from_numpy(x).cuda(), torch.from_numpy(G).cuda()
+        out = torch.empty((N, K, 13, 13), device="cuda")
+        dv = torch.empty((len(va),), device="cuda")
+        st = torch.cuda.current_stream().cuda_stream
+        sw.swconv_forward(plan, st, xd.data_ptr(), out.data_ptr())
+        sw.swconv_backward(plan, st, 0, gd.data_ptr(), 0, dv.data_ptr())
+        torch.cuda.synchronize()
+        grad = dv.cpu().numpy()
+        upd, rp2, ci2, va2, dev = gpu_prune(rp, ci, va, grad, 1e-4, 1e-3, 1e-4, 0.1)
+        upd_o, (rp_o, ci_o, va_o) = oracle.prune_step(rp, ci, va, grad, 1e-4, 1e-3, 1e-4, 0.1, np.float32)
+        np.testing.assert_array_equal(rp2, rp_o)
+        np.testing.assert_array_equal(va2.view(np.uint32), va_o.view(np.uint32))
+        assert 0 < rp2[-1] < len(va)
+        sw.swconv_set_weights_device(plan, st, dev[0].data_ptr(), dev[1].data_ptr(), dev[2].data_ptr())
+        sw.swconv_forward(plan, st, xd.data_ptr(), out.data_ptr())
+        torch.cuda.synchronize()
+        ref = oracle.forward_f64(x, rp_o, ci_o, va_o, K, m, 3, pad, want_VM=False)[0]
+        assert np.abs(out.cpu().numpy() - ref).max() <= 1e-4 * np.abs(ref).max()
+    finally:
+        sw.swconv_plan_destroy(plan)
