@@ -34,7 +34,7 @@
 // Readings where the paper is silent (kept identical in the GPU library's
 // documentation):
 //   * A, B, G are the standard minimal-filtering matrices for interpolation
-//     points {0, 1, -1, inf} (F(2,3)) and {0, 1, -1, 2, -2, inf} (F(4,3));
+//     points {0, 1, -1, inf} (F(2,3)) and {0, 1, -1, 2, -2, inf} (F(4,3), F(2,5));
 //     Section 3 only says the F(2x2,3x3) ones have entries 0, +-1, +-1/2.
 //   * position index p = i*t + j, i = row of the transformed tile.
 //   * tile index tau = (n*th + ty)*tw + tx, th = ceil(H_o/m), tw = ceil(W_o/m);
@@ -61,7 +61,7 @@ struct WinogradMatrices {
   int m, r, t;
   double AT[4][6];  // m x t   (A^T)
   double BT[6][6];  // t x t   (B^T)
-  double G[6][3];   // t x r
+  double G[6][5];   // t x r
 };
 
 bool winograd_matrices(int m, int r, WinogradMatrices* w) {
@@ -98,6 +98,30 @@ bool winograd_matrices(int m, int r, WinogradMatrices* w) {
       for (int j = 0; j < 3; ++j) w->G[i][j] = G[i][j];
     for (int i = 0; i < 4; ++i)
       for (int j = 0; j < 6; ++j) w->AT[i][j] = AT[i][j];
+    return true;
+  }
+  if (m == 2 && r == 5) {
+    // Same six interpolation points as F(4,3), {0, 1, -1, 2, -2, inf}: B^T depends on the points
+    // only and is the F(4,3) one; A^T[a][i] = p_i^a and G[i][j] = c_i p_i^j with the F(4,3)
+    // scalings c = (1/4, -1/6, -1/6, 1/24, 1/24), the point at infinity taking the last row of
+    // A^T and the highest filter coefficient.  (The paper names 5x5 layers, Section 6, without
+    // printing matrices; this is the construction its reference for the 3x3 ones uses.)
+    const double p[5] = {0, 1, -1, 2, -2};
+    const double c[5] = {1.0 / 4, -1.0 / 6, -1.0 / 6, 1.0 / 24, 1.0 / 24};
+    const double BT[6][6] = {{4, 0, -5, 0, 1, 0},  {0, -4, -4, 1, 1, 0}, {0, 4, -4, -1, 1, 0},
+                             {0, -2, -1, 2, 1, 0}, {0, 2, -1, -2, 1, 0}, {0, 4, 0, -5, 0, 1}};
+    for (int i = 0; i < 6; ++i)
+      for (int j = 0; j < 6; ++j) w->BT[i][j] = BT[i][j];
+    for (int i = 0; i < 5; ++i) {
+      double pw = 1;
+      for (int j = 0; j < 5; ++j) {
+        w->G[i][j] = c[i] * pw;
+        if (j < 2) w->AT[j][i] = pw;
+        pw *= p[i];
+      }
+    }
+    w->G[5][4] = 1;
+    w->AT[1][5] = 1;
     return true;
   }
   return false;
@@ -496,7 +520,7 @@ int oracle_wf_from_spatial_f64(int K, int C, int m, int r, const double* w, doub
   for (int k = 0; k < K; ++k)
     for (int c = 0; c < C; ++c) {
       const double* g = w + ((int64_t)k * C + c) * r * r;
-      double Gg[6][3];
+      double Gg[6][5];
       for (int i = 0; i < t; ++i)
         for (int v = 0; v < r; ++v) {
           double s = 0;

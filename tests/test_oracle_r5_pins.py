@@ -1,0 +1,111 @@
+"""Pins of the oracle for 5x5 kernels, F(2x2,5x5) (the paper times 3x3 and 5x5 layers, Section 6, and
+prints no matrices).  The layer is pinned to the definition it must reduce to: with W_F = G w G^T it equals
+the direct 5x5 convolution (brute force and a library routine), which fails for any wrong entry of A, B or
+G; the position order by the single-non-zero closed form; the backward pass by the adjoint identities and
+the direct-convolution gradients.  The matrices themselves are pinned as the Vandermonde construction on the
+points {0, 1, -1, 2, -2, inf}."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.signal
+
+import oracle
+from paper_1702_08597_amd import synth
+
+M, R, T = 2, 5, 6
+
+
+def dense_csr(P, K, C):
+    rowptr = (np.arange(P * K + 1, dtype=np.int64) * C).astype(np.int32)
+    return rowptr, np.tile(np.arange(C, dtype=np.int32), P * K)
+
+
+def test_matrices_are_the_vandermonde_construction_on_the_f43_points():
+    AT, BT, G = oracle.winograd_matrices(M, R)
+    assert AT.shape == (2, 6) and BT.shape == (6, 6) and G.shape == (6, 5)
+    _, BT43, G43 = oracle.winograd_matrices(4, 3)
+    np.testing.assert_array_equal(BT, BT43)                 # same points, same interpolation matrix
+    p = [Fraction(v) for v in (0, 1, -1, 2, -2)]
+    c = [G43[i, 0] for i in range(5)]                       # the scalings of the F(4,3) G (its first column)
+    for i in range(5):
+        for a in range(2):
+            assert AT[a, i] == float(p[i] ** a)
+        for j in range(5):
+            assert G[i, j] == c[i] * float(p[i] ** j)
+    np.testing.assert_array_equal(AT[:, 5], [0, 1])
+    np.testing.assert_array_equal(G[5], [0, 0, 0, 0, 1])
+    # 1-D minimal filtering identity F(2,5): A^T[(G g) . (B^T d)] = correlation
+    rng = np.random.default_rng(0)
+    d, g = rng.standard_normal(6), rng.standard_normal(5)
+    want = [np.dot(d[a:a + 5], g) for a in range(2)]
+    np.testing.assert_allclose(AT @ ((G @ g) * (BT @ d)), want, rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("pad", [0, 2])
+@pytest.mark.parametrize("N,C,K,H,W", [(1, 1, 1, 5, 5), (2, 3, 2, 9, 7), (1, 2, 3, 27, 27), (1, 1, 2, 6, 13)])
+def test_layer_with_GwGT_equals_direct_5x5_convolution(pad, N, C, K, H, W):
+    rng = np.random.default_rng(100 * pad + H + C)
+    x = rng.standard_normal((N, C, H, W))
+    w = rng.standard_normal((K, C, 5, 5))
+    wf = oracle.wf_from_spatial_f64(w, M)
+    rp, ci = dense_csr(36, K, C)
+    out = oracle.forward_f64(x, rp, ci, wf.reshape(-1), K, M, R, pad, want_VM=False)[0]
+    brute = oracle.direct_conv_f64(x, w, pad)
+    xp = np.pad(x, ((0, 0), (0, 0), (pad, pad), (pad, pad)))
+    lib = np.zeros_like(brute)
+    for n in range(N):
+        for k in range(K):
+            for c in range(C):
+                lib[n, k] += scipy.signal.correlate2d(xp[n, c], w[k, c], mode="valid")
+    scale = max(1.0, np.abs(lib).max())
+    assert np.abs(brute - lib).max() <= 1e-12 * scale
+    assert np.abs(out - lib).max() <= 1e-11 * scale
+
+
+def test_single_nonzero_closed_form_fixes_the_position_order():
+    N, C, K, H, W, pad = 1, 2, 2, 8, 6, 2
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((N, C, H, W))
+    AT, BT, _ = oracle.winograd_matrices(M, R)
+    i, j, k, c, wv = 1, 4, 1, 0, 0.75
+    rowptr = np.zeros(36 * K + 1, dtype=np.int32)
+    rowptr[(i * T + j) * K + k + 1:] = 1
+    out = oracle.forward_f64(x, rowptr, np.array([c], np.int32), np.array([wv]), K, M, R, pad, want_VM=False)[0]
+    xp = np.pad(x, ((0, 0), (0, 0), (pad, pad + 2), (pad, pad + 2)))
+    th, tw = -(-out.shape[2] // M), -(-out.shape[3] // M)
+    for ty in range(th):
+        for tx in range(tw):
+            d = xp[0, c, ty * M:ty * M + T, tx * M:tx * M + T]
+            y = wv * (BT @ d @ BT.T)[i, j] * np.outer(AT[:, i], AT[:, j])
+            got = out[0, k, ty * M:ty * M + M, tx * M:tx * M + M]
+            np.testing.assert_allclose(got, y[:got.shape[0], :got.shape[1]], rtol=0, atol=1e-12)
+    assert np.all(out[0, 0] == 0)
+
+
+@pytest.mark.parametrize("pad,H,W", [(2, 9, 9), (0, 8, 11), (1, 6, 7)])
+def test_backward_adjoint_identities_and_direct_convolution_gradients(pad, H, W):
+    rng = np.random.default_rng(300 + pad)
+    N, C, K = 2, 3, 4
+    x = rng.standard_normal((N, C, H, W))
+    Ho, Wo = H + 2 * pad - 4, W + 2 * pad - 4
+    G = rng.standard_normal((N, K, Ho, Wo))
+    rp, ci, va = synth.bernoulli_weights(36, K, C, 0.6, 301)
+    va = rng.standard_normal(va.shape)
+    out, V, Mm = oracle.forward_f64(x, rp, ci, va, K, M, R, pad)
+    din, dvals, dZ, dV = oracle.backward_f64(x, rp, ci, va, G, K, M, R, pad)
+    L = float((out * G).sum())
+    scale = np.abs(out).max() * np.abs(G).max() * out.size
+    for other in ((x * din).sum(), (va * dvals).sum(), (Mm * dZ).sum(), (V * dV).sum()):
+        assert abs(L - float(other)) <= 1e-12 * scale
+    # dense W_F = G w G^T: the input gradient is the direct convolution's
+    w = rng.standard_normal((K, C, 5, 5))
+    wf = oracle.wf_from_spatial_f64(w, M)
+    rpd, cid = dense_csr(36, K, C)
+    din2 = oracle.backward_f64(x, rpd, cid, wf.reshape(-1), G, K, M, R, pad, want_ZV=False)[0]
+    dxp = np.zeros((N, C, H + 2 * pad, W + 2 * pad))
+    for u in range(5):
+        for v in range(5):
+            dxp[:, :, u:u + Ho, v:v + Wo] += np.einsum("nkyx,kc->ncyx", G, w[:, :, u, v])
+    ref = dxp[:, :, pad:pad + H, pad:pad + W]
+    np.testing.assert_allclose(din2, ref, rtol=0, atol=1e-11 * np.abs(ref).max())
