@@ -18,13 +18,18 @@
  * Conventions (where the paper is silent, these readings are part of the contract):
  *   - fp32 data, int32 indices.  Unit stride and dilation, square r x r kernel, square m x m
  *     output tile (Section 3 assumes unit stride/dilation; A1=A2, B1=B2 when r=s, m=n).
- *   - Supported F(m x m, r x r): (m,r) = (2,3) and (4,3).  A, B are the standard
- *     minimal-filtering matrices for points {0,1,-1,inf} and {0,1,-1,2,-2,inf} (the paper defers
- *     to Lavin & Gray for their values):
+ *   - Supported F(m x m, r x r): (m,r) = (2,3), (4,3) and, for the 5x5 layers of Section 6
+ *     (Table 1), (2,5).  A, B are the standard minimal-filtering matrices for points {0,1,-1,inf}
+ *     and {0,1,-1,2,-2,inf} (the paper defers to Lavin & Gray for their values):
  *       F(2,3): B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1],  A^T = [1 1 1 0; 0 1 -1 -1]
  *       F(4,3): B^T = [4 0 -5 0 1 0; 0 -4 -4 1 1 0; 0 4 -4 -1 1 0; 0 -2 -1 2 1 0;
  *                      0 2 -1 -2 1 0; 0 4 0 -5 0 1]
  *               A^T = [1 1 1 1 1 0; 0 1 -1 2 -2 0; 0 1 1 4 4 0; 0 1 -1 8 -8 1]
+ *       F(2,5): B^T as F(4,3) (same six points),  A^T = [1 1 1 1 1 0; 0 1 -1 2 -2 1]
+ *               (for reference, the matching 6 x 5 filter transform has rows
+ *                [1/4 0 0 0 0], -1/6 [1 1 1 1 1], -1/6 [1 -1 1 -1 1], 1/24 [1 2 4 8 16],
+ *                1/24 [1 -2 4 -8 16], [0 0 0 0 1]; the library itself never applies it: W_F is
+ *                given in the Winograd domain)
  *   - Ho = H + 2*pad - r + 1, Wo likewise; th = ceil(Ho/m), tw = ceil(Wo/m); T = N*th*tw.
  *     Tile tau = (n*th + ty)*tw + tx reads input rows ty*m - pad ... ty*m - pad + t - 1 (zero
  *     outside the image: this covers both the convolution padding and a ragged last tile, per
@@ -218,6 +223,18 @@ int swconv_debug_export_weights(swconv_plan* plan, int32_t* rowptr, int32_t* col
  * weights were set.  Needs no GPU.
  */
 int swconv_debug_check_schedule(const swconv_plan* plan);
+
+/*
+ * Channel groups (the grouped 5x5 and 3x3 layers of AlexNet, Section 6): a plan made for the C
+ * input and K output channels of ONE group can work inside the tensors of the whole layer.  The
+ * strides are the distances, in floats, between consecutive images of the input / dL/dI tensor
+ * (in_stride >= C*H*W) and of the output / dL/dO tensor (out_stride >= K*Ho*Wo); 0 restores the
+ * dense default.  The caller then passes pointers to the group's first channel of image 0, e.g.
+ * in + g*C*H*W with in_stride = G*C*H*W.  Applies to every later forward and backward call;
+ * channels outside the group are neither read nor written.  Errors: EINVAL for a stride below
+ * the dense one or so large that the last image's offset leaves 2^40 floats.
+ */
+int swconv_plan_set_image_strides(swconv_plan* plan, int64_t in_stride, int64_t out_stride);
 
 /*
  * Sizes derived by the plan (any pointer may be NULL): positions P, tiles T, Ho, Wo.

@@ -18,7 +18,7 @@ EXPORTS = [
     "swconv_debug_copy_V", "swconv_debug_copy_M", "swconv_debug_export_weights", "swconv_plan_sizes",
     "swconv_plan_weight_stats", "swconv_debug_check_schedule",
     "swconv_backward", "swconv_debug_copy_dZ", "swconv_debug_copy_dV", "swconv_profile_backward",
-    "swconv_prune_step", "swconv_set_weights_device",
+    "swconv_prune_step", "swconv_set_weights_device", "swconv_plan_set_image_strides",
 ]
 
 _lib = None
@@ -58,6 +58,7 @@ def lib():
         L.swconv_plan_weight_stats.argtypes = [_vp, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
                                                ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int64)]
         L.swconv_debug_check_schedule.argtypes = [_vp]
+        L.swconv_plan_set_image_strides.argtypes = [_vp, ctypes.c_int64, ctypes.c_int64]
         L.swconv_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
         L.swconv_profile_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int, _f32p]
         L.swconv_prune_step.argtypes = [ctypes.c_int64, _vp, _vp, _vp, _vp] + [ctypes.c_float] * 4 + [_vp] * 5
@@ -176,6 +177,10 @@ def swconv_profile_forward(plan, stream, in_dev_ptr, out_dev_ptr, iters):
     _check(lib().swconv_profile_forward(plan, _vp(stream), _vp(in_dev_ptr), _vp(out_dev_ptr), int(iters),
                                         ms.ctypes.data_as(_f32p)), "swconv_profile_forward")
     return ms
+
+
+def swconv_plan_set_image_strides(plan, in_stride, out_stride):
+    _check(lib().swconv_plan_set_image_strides(plan, int(in_stride), int(out_stride)), "swconv_plan_set_image_strides")
 
 
 def swconv_plan_sizes(plan):

@@ -10,6 +10,7 @@
 #include <cstring>
 #include <new>
 #include <numeric>
+#include <type_traits>
 #include <vector>
 
 #include "swconv_backward_kernels.hpp"
@@ -146,11 +147,20 @@ int launch_kernel(void (*kern)(Params...), dim3 grid, dim3 block, size_t lds, co
   return SWCONV_OK;
 }
 
-template <int M>
+// Calls f(integral_constant<M>, integral_constant<R>) for the plan's F(m x m, r x r).
+template <typename F>
+int dispatch_mr(const swconv_plan* pl, F&& f) {
+  using std::integral_constant;
+  if (pl->r == 5) return f(integral_constant<int, 2>{}, integral_constant<int, 5>{});
+  return pl->m == 2 ? f(integral_constant<int, 2>{}, integral_constant<int, 3>{})
+                    : f(integral_constant<int, 4>{}, integral_constant<int, 3>{});
+}
+
+template <int M, int R>
 int launch_input_transform(const swconv_plan* pl, const LaunchTarget& to, const float* in) {
   dim3 grid(pl->g.Tp / 64, (pl->g.C + 3) / 4);
   const size_t lds = (size_t)4 * pl->g.in_area * sizeof(float);
-  auto kern = input_transform_kernel<M>;
+  auto kern = input_transform_kernel<M, R>;
   static bool attr_set = false;
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
@@ -159,11 +169,11 @@ int launch_input_transform(const swconv_plan* pl, const LaunchTarget& to, const 
   return launch_kernel(kern, grid, dim3(256), lds, to, in, pl->dV, pl->d_tiles, pl->d_blocks, pl->g);
 }
 
-template <int M>
+template <int M, int R>
 int launch_output_transform(const swconv_plan* pl, const LaunchTarget& to, float* out) {
   dim3 grid(pl->g.Tp / 64, (pl->g.K + 3) / 4);
   const size_t lds = (size_t)4 * pl->g.out_area * sizeof(float);
-  auto kern = output_transform_kernel<M>;
+  auto kern = output_transform_kernel<M, R>;
   static bool attr_set = false;
   if (!attr_set) {
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
@@ -207,9 +217,11 @@ int launch_spmm(const swconv_plan* pl, const PackedMatrix& pm, const LaunchTarge
 
 int launch_stage(const swconv_plan* pl, const LaunchTarget& to, int stage, const float* in, float* out) {
   switch (stage) {
-    case 0: return pl->m == 2 ? launch_input_transform<2>(pl, to, in) : launch_input_transform<4>(pl, to, in);
+    case 0:
+      return dispatch_mr(pl, [&](auto M, auto R) { return launch_input_transform<M(), R()>(pl, to, in); });
     case 1: return launch_spmm(pl, pl->fw, to, pl->dV, pl->g.v_bytes, pl->dM, pl->g.m_bytes);
-    default: return pl->m == 2 ? launch_output_transform<2>(pl, to, out) : launch_output_transform<4>(pl, to, out);
+    default:
+      return dispatch_mr(pl, [&](auto M, auto R) { return launch_output_transform<M(), R()>(pl, to, out); });
   }
 }
 
@@ -609,12 +621,12 @@ int prepare_weight_grad(swconv_plan* pl) {
   return SWCONV_OK;
 }
 
-template <int M>
+template <int M, int R>
 int launch_backward_transforms(swconv_plan* pl, const LaunchTarget& to, int which, const float* dout,
                                       float* din) {
   const Geometry& g = pl->g;
   if (which == 0) {  // dL/dZ = A dL/dO~ A^T into the M workspace
-    auto kern = output_grad_transform_kernel<M>;
+    auto kern = output_grad_transform_kernel<M, R>;
     static bool attr_set = false;
     if (!attr_set) {
       HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
@@ -624,11 +636,11 @@ int launch_backward_transforms(swconv_plan* pl, const LaunchTarget& to, int whic
                          dout, pl->dM, pl->d_tiles, pl->d_blocks, g);
   }
   if (which == 1)  // dL/dI~ = B dL/dI_F B^T, from the dL/dI_F workspace into the V workspace
-    return launch_kernel(input_grad_patch_kernel<M>, dim3(g.Tp / 64, (g.C + 3) / 4), dim3(256), 0, to, pl->dD, pl->dV,
+    return launch_kernel(input_grad_patch_kernel<M, R>, dim3(g.Tp / 64, (g.C + 3) / 4), dim3(256), 0, to, pl->dD, pl->dV,
                          g);
   const int cells = ((g.H - 1 + g.pad) / M + 1) * ((g.W - 1 + g.pad) / M + 1);
   const int64_t threads = (int64_t)g.N * g.C * cells;
-  return launch_kernel(input_grad_gather_kernel<M>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, to, pl->dV,
+  return launch_kernel(input_grad_gather_kernel<M, R>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, to, pl->dV,
                        din, g);
 }
 
@@ -662,11 +674,11 @@ int backward_ready(swconv_plan* pl, const float* in_dev, const float* dout_dev, 
 int launch_backward_stage(swconv_plan* pl, const LaunchTarget& to, int stage, const float* in_dev,
                           const float* dout_dev, float* din_dev, float* dvals_dev) {
   if (!backward_stage_runs(pl, stage, in_dev, din_dev, dvals_dev)) return SWCONV_OK;
-  const bool m2 = pl->m == 2;
   switch (stage) {
     case 0:
-      return m2 ? launch_backward_transforms<2>(pl, to, 0, dout_dev, nullptr)
-                : launch_backward_transforms<4>(pl, to, 0, dout_dev, nullptr);
+      return dispatch_mr(pl, [&](auto M, auto R) {
+        return launch_backward_transforms<M(), R()>(pl, to, 0, dout_dev, nullptr);
+      });
     case 1: return launch_stage(pl, to, 0, in_dev, nullptr);
     case 2:
       return launch_spmm_mode<true>(pl, pl->fw, to, pl->dV, pl->g.v_bytes, pl->dM, pl->g.m_bytes, pl->d_partial);
@@ -678,8 +690,9 @@ int launch_backward_stage(swconv_plan* pl, const LaunchTarget& to, int stage, co
     }
     case 4: return launch_spmm(pl, pl->bt, to, pl->dM, pl->g.m_bytes, pl->dD, pl->g.v_bytes);
     default:
-      return m2 ? launch_backward_transforms<2>(pl, to, stage - 4, nullptr, din_dev)
-                : launch_backward_transforms<4>(pl, to, stage - 4, nullptr, din_dev);
+      return dispatch_mr(pl, [&](auto M, auto R) {
+        return launch_backward_transforms<M(), R()>(pl, to, stage - 4, nullptr, din_dev);
+      });
   }
 }
 
@@ -702,7 +715,7 @@ const char* swconv_status_string(int status) {
 int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int m, int r, int pad) {
   if (!out) return SWCONV_EINVAL;
   if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || pad < 0 || m < 1 || r < 1) return SWCONV_EINVAL;
-  if (!((m == 2 && r == 3) || (m == 4 && r == 3))) return SWCONV_EUNSUPPORTED;
+  if (!((m == 2 && r == 3) || (m == 4 && r == 3) || (m == 2 && r == 5))) return SWCONV_EUNSUPPORTED;
   const int64_t Ho = (int64_t)H + 2 * pad - r + 1, Wo = (int64_t)W + 2 * pad - r + 1;
   if (Ho < 1 || Wo < 1) return SWCONV_EINVAL;
   const int t = m + r - 1, P = t * t;
@@ -748,6 +761,8 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   }
   g.wo_magic = (uint32_t)((((uint64_t)1 << 32) + g.Wo - 1) / g.Wo);
   g.m_shift = m == 4 ? 2 : 1;
+  g.in_image_stride = (int64_t)C * H * W;
+  g.out_image_stride = (int64_t)K * Ho * Wo;
   try {
     build_transform_tables(pl);
   } catch (const std::bad_alloc&) {
@@ -760,6 +775,21 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
     return SWCONV_EUNSUPPORTED;
   }
   *out = pl;
+  return SWCONV_OK;
+}
+
+int swconv_plan_set_image_strides(swconv_plan* pl, int64_t in_stride, int64_t out_stride) {
+  if (!pl) return SWCONV_EINVAL;
+  const Geometry& g = pl->g;
+  const int64_t in_min = (int64_t)g.C * g.H * g.W, out_min = (int64_t)g.K * g.Ho * g.Wo;
+  if (in_stride == 0) in_stride = in_min;
+  if (out_stride == 0) out_stride = out_min;
+  // the last image must still be addressable with the 40-bit bound plan_create checks
+  if (in_stride < in_min || out_stride < out_min || in_stride > ((int64_t)1 << 40) / g.N ||
+      out_stride > ((int64_t)1 << 40) / g.N)
+    return SWCONV_EINVAL;
+  pl->g.in_image_stride = in_stride;
+  pl->g.out_image_stride = out_stride;
   return SWCONV_OK;
 }
 

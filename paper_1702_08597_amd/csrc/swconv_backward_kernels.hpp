@@ -20,13 +20,13 @@ namespace swconv {
 // output transform, read instead of written), every lane gathers its m x m tile - zero where the
 // tile reaches past H_o x W_o: those outputs were dropped by psi and carry no gradient -
 // transforms it in registers and stores one value per position.
-template <int M>
+template <int M, int R>
 __global__ __launch_bounds__(256) void output_grad_transform_kernel(const float* __restrict__ dout,
                                                                     float* __restrict__ dZ,
                                                                     const TileInfo* __restrict__ tiles,
                                                                     const BlockImage* __restrict__ blocks,
                                                                     const Geometry g) {
-  constexpr int t = Wino<M>::t;
+  constexpr int t = Wino<M, R>::t;
   extern __shared__ float stage[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void output_grad_transform_kernel(const float*
       const BlockImage b = bi[sidx];
       if (b.n < 0) continue;
       // loads past the part's end return 0 (descriptor), so the padded tail of the run is zero
-      const __amdgpu_buffer_rsrc_t src = make_rsrc(dout + ((size_t)b.n * g.K + k) * plane + b.out_elem0,
+      const __amdgpu_buffer_rsrc_t src = make_rsrc(dout + (size_t)b.n * g.out_image_stride + k * plane + b.out_elem0,
                                                    (uint32_t)b.out_span * 4u);
       float* dst = my + b.out_off + lane;
       constexpr int EL = 4;  // loads per lane in flight
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void output_grad_transform_kernel(const float*
       }
   }
   float z[t][t];
-  output_grad_transform<M>(gr, z);
+  output_grad_transform<M, R>(gr, z);
   const __amdgpu_buffer_rsrc_t zr = make_rsrc(dZ, g.m_bytes);
   const uint32_t pstride = (uint32_t)g.K * (uint32_t)g.Tp * 4u;
   uint32_t soff = ((uint32_t)k * g.Tp + tau0) * 4u;
@@ -92,10 +92,10 @@ __global__ __launch_bounds__(256) void output_grad_transform_kernel(const float*
 // Eq. 6, second line.  A wave owns one input channel and 64 consecutive tiles: each lane reads the
 // t*t values dL/dI_F(c, tau, :, :) (256 contiguous bytes per wave and position), applies B . B^T in
 // registers and stores the t x t patch dL/dI~(c, tau, :, :), again one value per position.
-template <int M>
+template <int M, int R>
 __global__ __launch_bounds__(256) void input_grad_patch_kernel(const float* __restrict__ dV,
                                                                float* __restrict__ patches, const Geometry g) {
-  constexpr int t = Wino<M>::t;
+  constexpr int t = Wino<M, R>::t;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = blockIdx.y * 4 + wave;
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void input_grad_patch_kernel(const float* __re
       soff += pstride;
       asm volatile("" : "+s"(soff));
     }
-  input_grad_transform<M>(f, d);
+  input_grad_transform<M, R>(f, d);
   soff = row0;
 #pragma unroll
   for (int a = 0; a < t; ++a)
@@ -129,17 +129,18 @@ __global__ __launch_bounds__(256) void input_grad_patch_kernel(const float* __re
 // ---------------------------------------------------------------------------------------------
 // Eq. 6, third line, as a gather.  The input plane is cut into m x m cells aligned with the tile
 // stride: cell (qy, qx) holds the pixels y = qy*m - pad + ry, x = qx*m - pad + rx.  Every pixel of a
-// cell receives from the same at most 2 x 2 tiles (qy - dy, qx - dx), dy, dx in {0, 1}, the patch
-// entry (ry + m*dy, rx + m*dx) where that lies inside the t x t patch (t - m = r - 1 <= m).  A
+// cell receives from the same tiles (qy - dy, qx - dx), dy, dx in 0 .. (t-1)/m (one tile back for
+// the 3x3 filters, two for F(2x2,5x5)), the patch entry (ry + m*dy, rx + m*dx) where that lies
+// inside the t x t patch.  A
 // thread owns one cell of one (n, c) plane and lanes run over consecutive cells, i.e. consecutive
 // tiles, so every patch load of a wave is a contiguous run of one position plane and each patch
 // entry is read exactly once; each pixel is written once, its sum taken in ascending tile order.
 // Threads run over all cells of all (n, c) planes.
-template <int M>
+template <int M, int R>
 __global__ __launch_bounds__(256) void input_grad_gather_kernel(const float* __restrict__ patches,
                                                                 float* __restrict__ din, const Geometry g) {
-  constexpr int t = Wino<M>::t;
-  static_assert(t - M <= M, "a pixel lies in at most two tiles per dimension");
+  constexpr int t = Wino<M, R>::t;
+  constexpr int back = (t - 1) / M;  // tiles before its own that still cover a cell, per dimension
   const int cells_y = (g.H - 1 + g.pad) / M + 1, cells_x = (g.W - 1 + g.pad) / M + 1;
   const int cells = cells_y * cells_x;
   const uint32_t idx = blockIdx.x * 256u + threadIdx.x;  // (n, c) plane major, cells of a plane consecutive
@@ -154,12 +155,12 @@ __global__ __launch_bounds__(256) void input_grad_gather_kernel(const float* __r
   for (int ry = 0; ry < M; ++ry)
 #pragma unroll
     for (int rx = 0; rx < M; ++rx) acc[ry][rx] = 0.0f;
-  // tiles in ascending order: (qy-1, qx-1), (qy-1, qx), (qy, qx-1), (qy, qx)
+  // tiles in ascending order: (qy-back, qx-back), ..., (qy, qx)
 #pragma unroll
-  for (int dy = 1; dy >= 0; --dy) {
+  for (int dy = back; dy >= 0; --dy) {
     const int ty = qy - dy;
 #pragma unroll
-    for (int dx = 1; dx >= 0; --dx) {
+    for (int dx = back; dx >= 0; --dx) {
       const int tx = qx - dx;
       if (ty < 0 || ty >= g.th || tx < 0 || tx >= g.tw) continue;
       const uint32_t base = ((uint32_t)c * g.Tp + (uint32_t)(n * g.th + ty) * g.tw + tx) * 4u;
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(256) void input_grad_gather_kernel(const float* __r
         }
     }
   }
-  float* plane = din + (size_t)nc * g.H * g.W;
+  float* plane = din + (size_t)n * g.in_image_stride + (size_t)c * g.H * g.W;
 #pragma unroll
   for (int ry = 0; ry < M; ++ry) {
     const int y = qy * M - g.pad + ry;

@@ -44,6 +44,9 @@ struct Geometry {
   uint32_t v_bytes, m_bytes;  // sizes of the V and M workspaces (both below 4 GiB)
   uint32_t wo_magic;          // ceil(2^32 / Wo): e / Wo == umulhi(e, wo_magic) for every staged element index
   int m_shift;                // log2(m)
+  // floats between consecutive images of the input (and dL/dI) and of the output (and dL/dO):
+  // C*H*W and K*Ho*Wo for dense tensors, larger when the layer works on a channel group of them
+  int64_t in_image_stride, out_image_stride;
 };
 
 // V and M are addressed through buffer descriptors: address = base + scalar byte offset (the
@@ -143,12 +146,12 @@ __device__ __forceinline__ int xcd_contiguous_id(int bid, int nblocks) {
 // lies outside the image), transforms it in registers and stores one value per position:
 // 64 lanes -> 256 contiguous bytes of V[p][c][.], addressed as wave-uniform row + lane.
 // Block = 4 waves = 4 channels of the same tile block.
-template <int M>
+template <int M, int R>
 __global__ __launch_bounds__(256) void input_transform_kernel(const float* __restrict__ in, float* __restrict__ V,
                                                               const TileInfo* __restrict__ tiles,
                                                               const BlockImage* __restrict__ blocks,
                                                               const Geometry g) {
-  constexpr int t = Wino<M>::t;
+  constexpr int t = Wino<M, R>::t;
   extern __shared__ float stage[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -172,7 +175,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
         const BlockImage b = bi[sidx];
         const bool used = s0 + i < g.slots && b.n >= 0;
         span[i] = used ? b.in_span : 0;
-        src[i] = make_rsrc(in + ((size_t)max(b.n, 0) * g.C + c) * plane + b.in_elem0, (uint32_t)span[i] * 4u);
+        src[i] = make_rsrc(in + (size_t)max(b.n, 0) * g.in_image_stride + c * plane + b.in_elem0, (uint32_t)span[i] * 4u);
         dst[i] = my + b.in_off + lane;
         max_span = max(max_span, span[i]);
       }
@@ -231,7 +234,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
     }
   }
   float v[t][t];
-  input_transform<M>(d, v);
+  input_transform<M, R>(d, v);
   const __amdgpu_buffer_rsrc_t vr = make_rsrc(V, g.v_bytes);
   const uint32_t row0 = ((uint32_t)c * g.Tp + tau0) * 4u;        // wave-uniform byte offset, position 0
   const uint32_t pstride = (uint32_t)g.C * (uint32_t)g.Tp * 4u;  // bytes between positions
@@ -586,13 +589,13 @@ __global__ __launch_bounds__(NWAVES * 64, NWAVES == 12 ? 6 : 4) void spmm_kernel
 // rows; the wave then writes those rows out with lane-contiguous stores (whole image planes when
 // the block covers whole images).  Pixels of tiles that belong to a neighbouring block are
 // skipped.  Block = 4 waves = 4 output channels of the same tile block.
-template <int M>
+template <int M, int R>
 __global__ __launch_bounds__(256) void output_transform_kernel(const float* __restrict__ Mbuf,
                                                                float* __restrict__ out,
                                                                const TileInfo* __restrict__ tiles,
                                                                const BlockImage* __restrict__ blocks,
                                                                const Geometry g) {
-  constexpr int t = Wino<M>::t;
+  constexpr int t = Wino<M, R>::t;
   extern __shared__ float stage[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -615,7 +618,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
         asm volatile("" : "+s"(soff));
       }
     float y[M][M];
-    output_transform<M>(z, y);
+    output_transform<M, R>(z, y);
     const TileInfo ti = tiles[tau0 + lane];
     const int y0 = (int16_t)(ti.yx0 & 0xffff), x0 = ti.yx0 >> 16;
     // rows / columns of the tile inside the output (<= 0 for a padding tile, whose y0 is -32768)
@@ -635,7 +638,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
     const BlockImage b = bi[sidx];
     if (b.n < 0) continue;
     const float* src = my + b.out_off;
-    float* dst = out + ((size_t)b.n * g.K + k) * plane + b.out_elem0;
+    float* dst = out + (size_t)b.n * g.out_image_stride + k * plane + b.out_elem0;
     // stores past the part's end are dropped by the descriptor: no lane predicate
     const __amdgpu_buffer_rsrc_t orr = make_rsrc(dst, (uint32_t)b.out_span * 4u);
     if (b.whole) {

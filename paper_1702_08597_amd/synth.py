@@ -5,8 +5,8 @@ and random sparse Winograd-domain weights and lays the latter out as per-positio
 CSR.  Both the GPU library and the CPU oracle are fed the arrays it returns.
 
 The shapes, densities and value distributions stand in for the workloads of the
-paper's Section 6.2 (3x3 layers of an AlexNet pruned natively in the Winograd
-domain, Table 1 method A: 4-9 % non-zeros), whose trained weights and dataset
+paper's Section 6.2 (3x3 and 5x5 layers of an AlexNet pruned natively in the Winograd
+domain, Table 1 method A: 4-10 % non-zeros), whose trained weights and dataset
 are not available: post-ReLU-like activations ``max(0, N(0,1))``, iid Bernoulli
 masks, non-zeros ``N(0, sigma=0.05)``.
 """
@@ -24,6 +24,8 @@ CONFIGS = {
     "alexnet_conv4_n64_f4": dict(N=64, C=384, H=13, W=13, K=384, m=4, r=3, pad=1, density=0.10, seed=BASE_SEED + 3),
     "alexnet_conv5_n64_f4": dict(N=64, C=384, H=13, W=13, K=256, m=4, r=3, pad=1, density=0.10, seed=BASE_SEED + 4),
     "vgg_56_n32_f4": dict(N=32, C=256, H=56, W=56, K=256, m=4, r=3, pad=1, density=0.10, seed=BASE_SEED + 5),
+    # one of the two channel groups of AlexNet's 5x5 layer (Table 1: conv2, 90.6 % sparse under method A)
+    "alexnet_conv2g_n32_f2r5": dict(N=32, C=48, H=27, W=27, K=128, m=2, r=5, pad=2, density=0.094, seed=BASE_SEED + 7),
     "conv4_skewed_n64_f4": dict(N=64, C=384, H=13, W=13, K=384, m=4, r=3, pad=1, density=None, seed=BASE_SEED + 6),
 }
 BENCH_CONFIG = "alexnet_conv3_n32_f4"

@@ -35,7 +35,7 @@ def test_status_strings():
     ((1, 4, 8, 8, 4, 4, 3, -1), sw.SWCONV_EINVAL),
     ((1, 4, 2, 8, 4, 4, 3, 0), sw.SWCONV_EINVAL),      # Ho < 1
     ((1, 4, 8, 8, 4, 3, 3, 1), sw.SWCONV_EUNSUPPORTED),  # F(3,3)
-    ((1, 4, 8, 8, 4, 2, 5, 1), sw.SWCONV_EUNSUPPORTED),  # r = 5
+    ((1, 4, 8, 8, 4, 4, 5, 1), sw.SWCONV_EUNSUPPORTED),  # F(4,5): only F(2,5) is built for r = 5
     ((1, 4096, 8, 8, 4, 4, 3, 1), sw.SWCONV_EUNSUPPORTED),  # panel beyond LDS
 ])
 def test_plan_create_rejects(args, status):
@@ -51,7 +51,23 @@ def test_plan_sizes():
     pl = sw.swconv_plan_create(1, 256, 13, 13, 384, 2, 3, 1)
     assert sw.swconv_plan_sizes(pl) == (16, 49, 13, 13)
     sw.swconv_plan_destroy(pl)
+    pl = sw.swconv_plan_create(32, 48, 27, 27, 128, 2, 5, 2)   # F(2x2,5x5): t = 6
+    assert sw.swconv_plan_sizes(pl) == (36, 32 * 14 * 14, 27, 27)
+    sw.swconv_plan_destroy(pl)
     sw.swconv_plan_destroy(None)
+
+
+def test_image_strides_are_validated():
+    pl = sw.swconv_plan_create(2, 4, 6, 6, 3, 2, 3, 1)
+    try:
+        sw.swconv_plan_set_image_strides(pl, 2 * 4 * 36, 2 * 3 * 36)
+        sw.swconv_plan_set_image_strides(pl, 0, 0)                     # back to dense
+        for bad in ((4 * 36 - 1, 0), (0, 3 * 36 - 1), (-5, 0), (2 ** 40, 0), (0, 2 ** 40)):
+            with pytest.raises(sw.SwconvError) as e:
+                sw.swconv_plan_set_image_strides(pl, *bad)
+            assert e.value.status == sw.SWCONV_EINVAL
+    finally:
+        sw.swconv_plan_destroy(pl)
 
 
 def _tiny_plan():
