@@ -98,7 +98,11 @@ int swconv_set_weights(swconv_plan* plan, const int32_t* rowptr, const int32_t* 
 /*
  * Forward pass of Eq. 4 with the sparse weights: three kernels (Section 5's steps 1-3)
  * enqueued on `hip_stream` (a hipStream_t; NULL = the default stream).  Asynchronous: returns
- * after enqueueing, does not synchronise.
+ * after enqueueing, does not synchronise.  For m = 2 layers with at most 128 input channels
+ * whose rows have at most 32 stored entries (the 5x5 layer of Section 6) steps 2 and 3 run as
+ * ONE kernel that keeps the per-position products on chip (Section 5: a core that owns its
+ * tiles through all steps can fuse the second and third); the environment variable
+ * SWCONV_FUSE_OUTPUT=0, read by swconv_plan_create, keeps such a plan on three kernels.
  *   in_dev   DEVICE, N x C x H x W fp32, contiguous (W fastest), read-only.
  *   out_dev  DEVICE, N x K x Ho x Wo fp32, contiguous; every element is overwritten.
  * The two must not alias and must live on the device the weights were set on.  The plan owns
@@ -191,7 +195,8 @@ int swconv_debug_copy_dV(swconv_plan* plan, float* dV_host);
  * with a pair of HIP events that take the kernel's own start and end time stamps on that stream
  * (no extra packets between the kernels), synchronise, and return the mean duration of each
  * step in milliseconds.
- *   stage_ms  HOST, 3 floats: input transform, sparse product, output transform.
+ *   stage_ms  HOST, 3 floats: input transform, sparse product, output transform; when steps
+ *             2 and 3 run fused, the second is that kernel's time and the third is 0.
  * Blocks the host.  Errors as for swconv_forward; EINVAL for iters < 1.
  */
 int swconv_profile_forward(swconv_plan* plan, void* hip_stream, const float* in_dev, float* out_dev, int iters,
@@ -201,6 +206,8 @@ int swconv_profile_forward(swconv_plan* plan, void* hip_stream, const float* in_
  * Test hooks (not on the timed path).  They synchronise the device and copy the intermediates
  * of the last forward into caller buffers in the canonical layouts of the definition above.
  *   V_host  HOST, [P][C][T] fp32        M_host  HOST, [P][K][T] fp32
+ * After a forward pass with steps 2 and 3 fused M was never stored: swconv_debug_copy_M then runs
+ * step 2 alone on the V of that pass (default stream) before copying.
  * Errors: ESTATE when no forward has run; EHIP.
  */
 int swconv_debug_copy_V(swconv_plan* plan, float* V_host);

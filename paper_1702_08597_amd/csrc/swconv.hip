@@ -15,6 +15,7 @@
 
 #include "swconv_backward_kernels.hpp"
 #include "swconv_dense_mfma.hpp"
+#include "swconv_fused_kernels.hpp"
 #include "swconv_kernels.hpp"
 #include "swconv_prune_kernels.hpp"
 
@@ -82,6 +83,21 @@ struct PackedMatrix {
   RangeHeader* d_ranges = nullptr;
 };
 
+// W_F packed for the fused product + output transform kernel (m = 2, few input channels): rows in
+// their natural order, 64 per workgroup, one package of 16-step batches per position.
+struct FusedProduct {
+  bool eligible = false;  // the layer shape allows the kernel
+  bool ready = false;     // the current weights fit its format and are on the device
+  int KC = 0;             // row chunks of kFusedRows
+  int B = 0;              // batches per slice and position (the longest row decides)
+  std::vector<uint32_t> wpk;
+  std::vector<uint8_t> lens;
+  std::vector<OutTile> otiles;
+  uint32_t* d_wpk = nullptr;
+  uint8_t* d_lens = nullptr;
+  OutTile* d_otiles = nullptr;
+};
+
 struct swconv_plan {
   Geometry g{};
   int m = 0, r = 0, t = 0, P = 0;
@@ -90,6 +106,8 @@ struct swconv_plan {
 
   PackedMatrix fw;  // W_F: K rows, panels of C channels (forward)
   PackedMatrix bt;  // W_F^T: C rows, panels of K channels (backward, Eq. 6 first line); packed on first use
+  FusedProduct fz;  // W_F again, for the kernel that runs steps 2 and 3 together
+  bool m_current = false;  // the M workspace holds the products of the last forward pass
   bool bt_supported = false, bt_current = false;
 
   // host-built index tables of the transform kernels
@@ -119,8 +137,9 @@ int ensure_workspace(swconv_plan* pl) {
   if (ndev < 1) return SWCONV_EHIP;
   const size_t vbytes = (size_t)pl->P * pl->g.C * pl->g.Tp * sizeof(float);
   const size_t mbytes = (size_t)pl->P * pl->g.K * pl->g.Tp * sizeof(float);
-  HIP_TRY(hipMalloc((void**)&pl->dV, vbytes));
-  HIP_TRY(hipMalloc((void**)&pl->dM, mbytes));
+  // a call that failed half way left its buffers in the plan: take them up again
+  if (!pl->dV) HIP_TRY(hipMalloc((void**)&pl->dV, vbytes));
+  if (!pl->dM) HIP_TRY(hipMalloc((void**)&pl->dM, mbytes));
   HIP_TRY(hipMemset(pl->dV, 0, vbytes));
   HIP_TRY(hipMemset(pl->dM, 0, mbytes));
   int rc;
@@ -215,7 +234,41 @@ int launch_spmm(const swconv_plan* pl, const PackedMatrix& pm, const LaunchTarge
   return launch_spmm_mode<false>(pl, pm, to, X, x_bytes, Y, y_bytes, nullptr);
 }
 
+template <int R, int PP>
+int launch_product_output_t(const swconv_plan* pl, const LaunchTarget& to, float* out) {
+  const FusedProduct& fz = pl->fz;
+  const Geometry& g = pl->g;
+  const size_t lds = (size_t)2 * ((size_t)g.C * kTileBlock * sizeof(float) + (size_t)kFusedWaves * fz.B * 512) + 1024;
+  auto kern = product_output_kernel<R, PP>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
+    attr_set = true;
+  }
+  const int n_wgs = pl->n_tau_blocks * fz.KC;
+  return launch_kernel(kern, dim3(n_wgs), dim3(kFusedWaves * 64), lds, to, (const float*)pl->dV, out,
+                       (const uint32_t*)fz.d_wpk, (uint32_t)(fz.wpk.size() * sizeof(uint32_t)),
+                       (const uint8_t*)fz.d_lens, (const OutTile*)fz.d_otiles, g.C, g.K, g.Tp, fz.KC, fz.B, n_wgs,
+                       g.v_bytes, (uint32_t)(g.Ho * g.Wo), g.Wo, (uint32_t)g.out_image_stride,
+                       (uint32_t)((int64_t)g.N * g.out_image_stride * (int64_t)sizeof(float)));
+}
+
+int launch_product_output(const swconv_plan* pl, const LaunchTarget& to, float* out) {
+  const bool one_piece = pl->g.C * (kTileBlock / 4) <= kFusedWaves * 64;
+  if (pl->r == 3)
+    return one_piece ? launch_product_output_t<3, 1>(pl, to, out) : launch_product_output_t<3, 2>(pl, to, out);
+  return one_piece ? launch_product_output_t<5, 1>(pl, to, out) : launch_product_output_t<5, 2>(pl, to, out);
+}
+
+// The forward pass is three kernels, or two where steps 2 and 3 run fused.
+bool fused_runs(const swconv_plan* pl) {
+  // its output stores use 32-bit byte offsets from the output pointer
+  return pl->fz.ready && (int64_t)pl->g.N * pl->g.out_image_stride * (int64_t)sizeof(float) < ((int64_t)1 << 32) - 256;
+}
+bool forward_stage_runs(const swconv_plan* pl, int stage) { return stage < 2 || !fused_runs(pl); }
+
 int launch_stage(const swconv_plan* pl, const LaunchTarget& to, int stage, const float* in, float* out) {
+  if (stage == 1 && fused_runs(pl)) return launch_product_output(pl, to, out);
   switch (stage) {
     case 0:
       return dispatch_mr(pl, [&](auto M, auto R) { return launch_input_transform<M(), R()>(pl, to, in); });
@@ -275,9 +328,63 @@ void build_transform_tables(swconv_plan* pl) {
         ti.yx0 = (int32_t)(((uint32_t)y0 & 0xffffu) | ((uint32_t)x0 << 16));
         ti.ylim = (int32_t)((uint32_t)y_lo | ((uint32_t)(y_hi - 1) << 16));
         ti.out_org = bi.out_off + (ty * m - oy_lo) * g.Wo + tx * m;
+        if (pl->fz.eligible) {
+          OutTile& ot = pl->fz.otiles[(size_t)base + tl];
+          ot.n = (uint32_t)n;
+          ot.pix = (uint32_t)(ty * m * g.Wo + tx * m);
+          ot.valid = (uint32_t)std::min(m, g.Ho - ty * m) | ((uint32_t)std::min(m, g.Wo - tx * m) << 16);
+        }
       }
     }
   }
+}
+
+// Packs W_F for the fused kernel: rows in natural order; slice s of position p = rows 4s .. 4s+3,
+// workgroup chunk kc = slices 16 kc .. 16 kc + 15.  Not ready (and the three-kernel path runs) when
+// a row is longer than the kernel's batches hold.
+void pack_fused(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, const float* vals) {
+  FusedProduct& fz = pl->fz;
+  fz.ready = false;
+  if (!fz.eligible) return;
+  const int P = pl->P, K = pl->g.K;
+  int32_t longest = 0;
+  for (int64_t i = 0; i < (int64_t)P * K; ++i) longest = std::max(longest, rowptr[i + 1] - rowptr[i]);
+  fz.KC = (K + kFusedRows - 1) / kFusedRows;
+  fz.B = std::max(1, (longest + kBatchSteps - 1) / kBatchSteps);
+  if (fz.B > kFusedMaxBatches) return;
+  const int spp = fz.KC * kFusedWaves;
+  const size_t dwords = (size_t)P * fz.KC * fz.B * kFusedWaves * 128;
+  if (dwords * 4 >= ((size_t)1 << 32) - 4096) return;
+  fz.wpk.assign(dwords, 0u);
+  fz.lens.assign((size_t)P * spp, 0);
+  const uint32_t row_bytes = (uint32_t)kTileBlock * sizeof(float);
+  for (int p = 0; p < P; ++p)
+    for (int k = 0; k < K; ++k) {
+      const int sl = k / kSliceRows, q = k % kSliceRows, kc = sl / kFusedWaves, w = sl % kFusedWaves;
+      const int32_t q0 = rowptr[(int64_t)p * K + k], len = rowptr[(int64_t)p * K + k + 1] - q0;
+      uint8_t& steps = fz.lens[(size_t)p * spp + sl];
+      steps = std::max<uint8_t>(steps, (uint8_t)((len + kStepGroup - 1) / kStepGroup * kStepGroup));
+      for (int32_t e = 0; e < len; ++e) {
+        const size_t batch = (((size_t)p * fz.KC + kc) * fz.B + e / kBatchSteps) * kFusedWaves + w;
+        uint32_t* entry = &fz.wpk[batch * 128 + ((size_t)q * kBatchSteps + e % kBatchSteps) * 2];
+        entry[0] = (uint32_t)colidx[q0 + e] * row_bytes;
+        std::memcpy(&entry[1], &vals[q0 + e], sizeof(float));
+      }
+    }
+  fz.ready = true;
+}
+
+int upload_fused(swconv_plan* pl) {
+  FusedProduct& fz = pl->fz;
+  if (!fz.ready) return SWCONV_OK;
+  fz.ready = false;
+  int rc;
+  if ((rc = upload(&fz.d_wpk, fz.wpk))) return rc;
+  if ((rc = upload(&fz.d_lens, fz.lens))) return rc;
+  if (!fz.d_otiles && (rc = upload(&fz.d_otiles, fz.otiles))) return rc;
+  HIP_TRY(hipDeviceSynchronize());
+  fz.ready = true;
+  return SWCONV_OK;
 }
 
 // Validate the caller's CSR; returns SWCONV_OK or SWCONV_EINVAL.
@@ -763,7 +870,12 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   g.m_shift = m == 4 ? 2 : 1;
   g.in_image_stride = (int64_t)C * H * W;
   g.out_image_stride = (int64_t)K * Ho * Wo;
+  // steps 2 and 3 in one kernel: m = 2 (16 output accumulators per lane) and a panel of at most
+  // kFusedMaxPieces 16-byte pieces per thread
+  pl->fz.eligible = m == 2 && C * (kTileBlock / 4) <= kFusedMaxPieces * kFusedWaves * 64 &&
+                    env_int("SWCONV_FUSE_OUTPUT", 1) != 0;
   try {
+    if (pl->fz.eligible) pl->fz.otiles.assign((size_t)g.Tp, OutTile{0, 0u, 0u, 0u});
     build_transform_tables(pl);
   } catch (const std::bad_alloc&) {
     delete pl;
@@ -800,6 +912,9 @@ void swconv_plan_destroy(swconv_plan* pl) {
     if (b) (void)hipFree(b);
   free_packed(&pl->fw);
   free_packed(&pl->bt);
+  void* fused[] = {pl->fz.d_wpk, pl->fz.d_lens, pl->fz.d_otiles};
+  for (void* b : fused)
+    if (b) (void)hipFree(b);
   delete pl;
 }
 
@@ -810,15 +925,19 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   size_grid(&pl->fw);
   pl->bt_current = false;
   pl->index_current = false;
+  pl->fz.ready = false;
   try {
     pack_matrix(&pl->fw, pl->P, pl->n_tau_blocks, rowptr, colidx, vals);
+    pack_fused(pl, rowptr, colidx, vals);
   } catch (const std::bad_alloc&) {
     pl->fw.packed = false;
     pl->fw.on_device = false;
+    pl->fz.ready = false;
     return SWCONV_ENOMEM;
   }
   if ((rc = ensure_workspace(pl))) return rc;
-  return upload_packed(&pl->fw);
+  if ((rc = upload_packed(&pl->fw))) return rc;
+  return upload_fused(pl);
 }
 
 int swconv_forward(swconv_plan* pl, void* hip_stream, const float* in_dev, float* out_dev) {
@@ -826,10 +945,12 @@ int swconv_forward(swconv_plan* pl, void* hip_stream, const float* in_dev, float
   if (!pl->fw.on_device) return SWCONV_ESTATE;
   const LaunchTarget to{(hipStream_t)hip_stream, nullptr, nullptr};
   for (int stage = 0; stage < 3; ++stage) {
+    if (!forward_stage_runs(pl, stage)) continue;
     int rc = launch_stage(pl, to, stage, in_dev, out_dev);
     if (rc) return rc;
   }
   pl->ran_forward = true;
+  pl->m_current = !fused_runs(pl);
   return SWCONV_OK;
 }
 
@@ -845,6 +966,7 @@ int swconv_profile_forward(swconv_plan* pl, void* hip_stream, const float* in_de
     if (hipEventCreate(&e) != hipSuccess) rc = SWCONV_EHIP;
   for (int it = 0; it < iters && !rc; ++it)
     for (int stage = 0; stage < 3 && !rc; ++stage) {
+      if (!forward_stage_runs(pl, stage)) continue;
       hipEvent_t* e = &ev[((size_t)it * 3 + stage) * 2];
       rc = launch_stage(pl, LaunchTarget{st, e[0], e[1]}, stage, in_dev, out_dev);
     }
@@ -853,6 +975,7 @@ int swconv_profile_forward(swconv_plan* pl, void* hip_stream, const float* in_de
     double sum[3] = {0, 0, 0};
     for (int it = 0; it < iters && !rc; ++it)
       for (int stage = 0; stage < 3; ++stage) {
+        if (!forward_stage_runs(pl, stage)) continue;
         hipEvent_t* e = &ev[((size_t)it * 3 + stage) * 2];
         float ms = 0;
         if (hipEventElapsedTime(&ms, e[0], e[1]) != hipSuccess) {
@@ -864,6 +987,7 @@ int swconv_profile_forward(swconv_plan* pl, void* hip_stream, const float* in_de
     if (!rc)
       for (int stage = 0; stage < 3; ++stage) stage_ms[stage] = (float)(sum[stage] / iters);
     pl->ran_forward = true;
+    pl->m_current = !fused_runs(pl);
   }
   for (auto& e : ev)
     if (e) (void)hipEventDestroy(e);
@@ -987,6 +1111,12 @@ int swconv_debug_copy_V(swconv_plan* pl, float* V_host) {
 int swconv_debug_copy_M(swconv_plan* pl, float* M_host) {
   if (!pl || !M_host) return SWCONV_EINVAL;
   if (!pl->ran_forward) return SWCONV_ESTATE;
+  if (!pl->m_current) {  // the fused kernel kept the products on chip: run step 2 alone on the V of that pass
+    HIP_TRY(hipDeviceSynchronize());
+    int rc = launch_spmm(pl, pl->fw, LaunchTarget{nullptr, nullptr, nullptr}, pl->dV, pl->g.v_bytes, pl->dM, pl->g.m_bytes);
+    if (rc) return rc;
+    pl->m_current = true;
+  }
   return copy_padded_to_host(pl->dM, M_host, (size_t)pl->P * pl->g.K, pl->g.T, pl->g.Tp);
 }
 
@@ -1064,6 +1194,7 @@ int swconv_forward_dense(swconv_plan* pl, void* hip_stream, const float* in_dev,
   rc = launch_stage(pl, to, 2, in_dev, out_dev);
   if (rc) return rc;
   pl->ran_forward = true;
+  pl->m_current = true;
   return SWCONV_OK;
 }
 

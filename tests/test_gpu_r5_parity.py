@@ -150,6 +150,64 @@ def test_channel_groups_inside_the_whole_layers_tensors(m, r, pad, H):
     assert not np.isnan(got_out).any() and not np.isnan(got_din).any()
 
 
+FUSED = [
+    # m = 2 layers with few input channels run steps 2 and 3 in one kernel: r, N, C, H, W, K, pad, density
+    (5, 3, 48, 27, 27, 128, 2, 0.1),    # the conv2 group's shape, two row chunks
+    (5, 2, 64, 9, 9, 65, 2, 0.3),       # one panel piece per thread exactly, rows longer than one batch, ragged chunk
+    (5, 2, 100, 8, 8, 5, 2, 0.15),      # two pieces per thread, two batches
+    (3, 4, 128, 13, 13, 130, 1, 0.1),   # F(2x2,3x3), the widest panel the kernel takes
+    (3, 9, 19, 13, 13, 10, 1, 0.0),     # no stored entries at all
+]
+
+
+@pytest.mark.parametrize("r,N,C,H,W,K,pad,density", FUSED)
+def test_fused_product_and_output_transform_against_oracle_and_three_kernel_path(r, N, C, H, W, K, pad, density,
+                                                                                 monkeypatch):
+    print("fused case r=%d N=%d C=%d H=%d W=%d K=%d" % (r, N, C, H, W, K), flush=True)
+    Pn = (r + 1) ** 2
+    x = synth.activations(N, C, H, W, 8100 + C)
+    rp, ci, va = synth.bernoulli_weights(Pn, K, C, density, 8200 + K)
+    o64, _, _ = oracle.forward_f64(x, rp, ci, va, K, 2, r, pad, want_VM=False)
+    xd = torch.from_numpy(x).cuda()
+    outs = []
+    for fuse in (1, 0):
+        monkeypatch.setenv("SWCONV_FUSE_OUTPUT", str(fuse))
+        plan = sw.swconv_plan_create(N, C, H, W, K, 2, r, pad)
+        try:
+            sw.swconv_set_weights(plan, rp, ci, va)
+            out = torch.full(o64.shape, float("nan"), dtype=torch.float32, device="cuda")
+            ms = sw.swconv_profile_forward(plan, 0, xd.data_ptr(), out.data_ptr(), 2)
+            assert (ms[2] == 0) == (fuse == 1), "which kernels ran"
+            out.fill_(float("nan"))
+            sw.swconv_forward(plan, 0, xd.data_ptr(), out.data_ptr())
+            torch.cuda.synchronize()
+            outs.append(out.cpu().numpy())
+        finally:
+            sw.swconv_plan_destroy(plan)
+    for o in outs:
+        assert not np.isnan(o).any()
+        assert relerr(o, o64) <= RTOL
+    assert relerr(outs[0], outs[1].astype(np.float64)) <= 1e-5
+
+
+def test_rows_longer_than_the_fused_kernels_batches_fall_back():
+    N, C, H, W, K = 2, 60, 9, 9, 8
+    x = synth.activations(N, C, H, W, 8300)
+    rp, ci, va = synth.bernoulli_weights(36, K, C, 0.9, 8301)     # rows of about 54 entries
+    o64, _, _ = oracle.forward_f64(x, rp, ci, va, K, 2, 5, 2, want_VM=False)
+    plan = sw.swconv_plan_create(N, C, H, W, K, 2, 5, 2)
+    try:
+        sw.swconv_set_weights(plan, rp, ci, va)
+        xd = torch.from_numpy(x).cuda()
+        out = torch.full(o64.shape, float("nan"), dtype=torch.float32, device="cuda")
+        ms = sw.swconv_profile_forward(plan, 0, xd.data_ptr(), out.data_ptr(), 2)
+        assert ms[2] > 0
+        torch.cuda.synchronize()
+        assert relerr(out.cpu().numpy(), o64) <= RTOL
+    finally:
+        sw.swconv_plan_destroy(plan)
+
+
 def test_other_filter_sizes_are_refused():
     for m, r in ((4, 5), (2, 7), (3, 3), (6, 3)):
         with pytest.raises(sw.SwconvError) as e:
