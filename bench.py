@@ -90,8 +90,13 @@ def run_backward(args, sw, synth, torch, np, plan, cfg, name, x, xd, rp, ci, va,
     stage_ms = sw.swconv_profile_backward(*a, args.steps)
     st = sw.swconv_plan_weight_stats(plan)
     models = backward_stage_models(cfg, nnz, st["padded_nnz"])
+    names = list(sw.BACKWARD_STAGES)
+    if stage_ms[6] == 0 and stage_ms[5] > 0:
+        # Eq. 6's last two lines ran as one kernel (image planes in LDS, no patch buffer)
+        names[5] = "input_grad_kernel"
+        models[5] = dict(bytes=4 * (cfg["P"] * cfg["C"] * cfg["T"] + cfg["N"] * cfg["C"] * cfg["H"] * cfg["W"]), flops=0)
     stages = []
-    for nm, ms, mdl in zip(sw.BACKWARD_STAGES, stage_ms.tolist(), models):
+    for nm, ms, mdl in zip(names, stage_ms.tolist(), models):
         gbs = mdl["bytes"] / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
         tfl = mdl["flops"] / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
         stages.append({"kernel": nm, "ms": round(ms, 6), "alg_bytes": mdl["bytes"], "alg_flops": mdl["flops"],

@@ -120,6 +120,10 @@ struct swconv_plan {
   bool on_device = false, dense_on_device = false, ran_forward = false;
   float *dV = nullptr, *dM = nullptr;
   float* dD = nullptr;        // backward pass: dL/dI_F, [P][C][Tp]
+  // Eq. 6's last two lines as one kernel when G whole image planes per wave fit LDS
+  int grad_images_per_group = 0;  // 0: the patch + gather kernels run instead
+  std::vector<GradTile> gtiles;   // Tp
+  GradTile* d_gtiles = nullptr;
   float* d_partial = nullptr; // backward pass: [tile blocks][stream entries of W_F] partial dot products
   size_t partial_floats = 0;
   int32_t* d_entry_index = nullptr;
@@ -704,6 +708,7 @@ int prepare_backward(swconv_plan* pl) {
     HIP_TRY(hipMalloc((void**)&pl->dD, pl->g.v_bytes));
     HIP_TRY(hipMemset(pl->dD, 0, pl->g.v_bytes));
   }
+  if (pl->grad_images_per_group > 0 && !pl->d_gtiles && (rc = upload(&pl->d_gtiles, pl->gtiles))) return rc;
   pl->bt_current = true;
   return SWCONV_OK;
 }
@@ -742,6 +747,18 @@ int launch_backward_transforms(swconv_plan* pl, const LaunchTarget& to, int whic
     return launch_kernel(kern, dim3(g.Tp / 64, (g.K + 3) / 4), dim3(256), (size_t)4 * g.out_area * sizeof(float), to,
                          dout, pl->dM, pl->d_tiles, pl->d_blocks, g);
   }
+  if (which == 1 && pl->grad_images_per_group > 0) {  // both remaining steps at once, planes in LDS
+    const int G = pl->grad_images_per_group;
+    const size_t lds = (size_t)4 * (((size_t)G * g.H * g.W + 63) / 64 * 64 + 64) * sizeof(float);
+    auto kern = input_grad_kernel<M, R>;
+    static bool attr_set = false;
+    if (!attr_set) {
+      HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
+      attr_set = true;
+    }
+    return launch_kernel(kern, dim3((g.N + G - 1) / G, (g.C + 3) / 4), dim3(256), lds, to, (const float*)pl->dD, din,
+                         (const GradTile*)pl->d_gtiles, G, g);
+  }
   if (which == 1)  // dL/dI~ = B dL/dI_F B^T, from the dL/dI_F workspace into the V workspace
     return launch_kernel(input_grad_patch_kernel<M, R>, dim3(g.Tp / 64, (g.C + 3) / 4), dim3(256), 0, to, pl->dD, pl->dV,
                          g);
@@ -764,6 +781,7 @@ constexpr int kBackwardStages = 7;
 bool backward_stage_runs(const swconv_plan* pl, int stage, const float* in, const float* din, const float* dvals) {
   if (stage == 1 && !in) return false;  // I_F of the last forward pass is still in the V workspace
   if (stage >= 1 && stage <= 3) return dvals != nullptr && pl->fw.nnz > 0;
+  if (stage == 6 && pl->grad_images_per_group > 0) return false;  // stage 5 did both
   if (stage >= 5) return din != nullptr;
   return true;
 }
@@ -881,6 +899,32 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
     delete pl;
     return SWCONV_ENOMEM;
   }
+  // backward pass, Eq. 6 second and third line in one kernel: G = 64 / (tiles per image) whole
+  // images per wave (at least one), if four waves' planes fit LDS
+  {
+    const int G = (int)std::min<int64_t>(N, std::max<int64_t>(1, 64 / g.tpi));
+    const int64_t wave_floats = ((int64_t)G * H * W + 63) / 64 * 64 + 64;
+    // (with patches reaching two tiles back, F(2x2,5x5), its nine phases measured slower than the two kernels)
+    if (4 * wave_floats * (int64_t)sizeof(float) <= kMaxLdsBytes && (t - 1) / m == 1 &&
+        env_int("SWCONV_FUSE_INPUT_GRAD", 1) != 0) {
+      try {
+        GradTile none;
+        none.org = 0;
+        none.yx0 = (int32_t)0x80008000u;
+        pl->gtiles.assign((size_t)g.Tp, none);
+        for (int64_t tau = 0; tau < T; ++tau) {
+          const int n = (int)(tau / g.tpi), tl = (int)(tau % g.tpi), ty = tl / g.tw, tx = tl % g.tw;
+          const int y0 = ty * m - pad, x0 = tx * m - pad;
+          pl->gtiles[(size_t)tau].org = (n % G) * H * W;
+          pl->gtiles[(size_t)tau].yx0 = (int32_t)(((uint32_t)y0 & 0xffffu) | ((uint32_t)x0 << 16));
+        }
+        pl->grad_images_per_group = G;
+      } catch (const std::bad_alloc&) {
+        delete pl;
+        return SWCONV_ENOMEM;
+      }
+    }
+  }
   // LDS staging areas of the transform kernels (four waves per workgroup)
   if ((int64_t)4 * std::max(g.in_area, g.out_area) * (int64_t)sizeof(float) > kMaxLdsBytes) {
     delete pl;
@@ -912,7 +956,7 @@ void swconv_plan_destroy(swconv_plan* pl) {
     if (b) (void)hipFree(b);
   free_packed(&pl->fw);
   free_packed(&pl->bt);
-  void* fused[] = {pl->fz.d_wpk, pl->fz.d_lens, pl->fz.d_otiles};
+  void* fused[] = {pl->fz.d_wpk, pl->fz.d_lens, pl->fz.d_otiles, pl->d_gtiles};
   for (void* b : fused)
     if (b) (void)hipFree(b);
   delete pl;

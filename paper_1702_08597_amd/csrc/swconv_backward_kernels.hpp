@@ -187,6 +187,101 @@ __global__ __launch_bounds__(256) void input_grad_gather_kernel(const float* __r
 }
 
 // ---------------------------------------------------------------------------------------------
+// Eq. 6, second and third line in one kernel, for images whose planes fit LDS: no patch buffer.
+// A wave owns one input channel and a group of G whole images (G = 64 / tiles per image, at least
+// 1), whose planes it keeps in LDS.  In passes of 64 consecutive tiles every lane reads the t*t
+// values dL/dI_F(c, tau, :, :), applies B . B^T in registers and adds its t x t patch into the
+// plane.  Patches of tiles closer than t pixels overlap, so the additions run in (back+1)^2
+// phases, phase (ty mod (back+1), tx mod (back+1)): the tiles of one phase are disjoint, LDS
+// executes a wave's operations in order, and every pixel therefore receives its terms in a fixed
+// order.  Then the wave writes its planes with lane-contiguous stores.  Block = 4 waves = 4
+// channels of the same image group.
+struct GradTile {
+  int32_t org;  // float offset of pixel (0, 0) of the tile's image inside the wave's LDS area
+  int32_t yx0;  // as TileInfo::yx0; y0 = x0 = -32768 for tiles past the last image
+};
+
+template <int M, int R>
+__global__ __launch_bounds__(256) void input_grad_kernel(const float* __restrict__ dV, float* __restrict__ din,
+                                                         const GradTile* __restrict__ gtiles, int images_per_group,
+                                                         const Geometry g) {
+  constexpr int t = Wino<M, R>::t;
+  constexpr int back = (t - 1) / M, PH = back + 1;
+  extern __shared__ float stage[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = blockIdx.y * 4 + wave;
+  if (c >= g.C) return;  // no barrier in this kernel: waves are independent
+  const int n0 = blockIdx.x * images_per_group;
+  const int n_img = min(images_per_group, g.N - n0);
+  const int plane = g.H * g.W;
+  const int area = images_per_group * plane;
+  const int area_padded = (area + 63) / 64 * 64;  // the wave's planes, then one spare float per lane
+  float* my = stage + (size_t)wave * (area_padded + 64);
+  for (int e = lane; e < area; e += 64) my[e] = 0.0f;
+  const __amdgpu_buffer_rsrc_t src = make_rsrc(dV, g.v_bytes);
+  const uint32_t pstride = (uint32_t)g.C * (uint32_t)g.Tp * 4u;
+  const int tau0 = n0 * g.tpi, tau_end = tau0 + n_img * g.tpi;
+  for (int base = tau0; base < tau_end; base += 64) {
+    const int tau = base + lane;
+    const bool live = tau < tau_end;
+    // lanes past the group's last tile are parked past the end of the buffer: they read zeros
+    const uint32_t voff = live ? ((uint32_t)c * g.Tp + (uint32_t)tau) * 4u : 0xfffffff0u;
+    float f[t][t], d[t][t];
+    uint32_t soff = 0;
+#pragma unroll
+    for (int i = 0; i < t; ++i)
+#pragma unroll
+      for (int j = 0; j < t; ++j) {
+        f[i][j] = buffer_load_f32(src, voff, soff);
+        soff += pstride;
+        asm volatile("" : "+s"(soff));
+      }
+    const GradTile gt = gtiles[live ? tau : tau0];
+    input_grad_transform<M, R>(f, d);
+    const int y0 = (int16_t)(gt.yx0 & 0xffff), x0 = gt.yx0 >> 16;
+    const int ty = (y0 + g.pad) >> g.m_shift, tx = (x0 + g.pad) >> g.m_shift;
+    const int phase = live ? (ty % PH) * PH + tx % PH : -1;
+    // LDS index of every patch entry; entries outside the image go to a spare float of the lane
+    const int spare = area_padded + lane;
+    const int org = gt.org + y0 * g.W + x0;
+    int at[t][t];
+#pragma unroll
+    for (int a = 0; a < t; ++a) {
+      const bool yok = y0 + a >= 0 && y0 + a < g.H;
+#pragma unroll
+      for (int b = 0; b < t; ++b) at[a][b] = (yok && x0 + b >= 0 && x0 + b < g.W) ? org + a * g.W + b : spare;
+    }
+#pragma unroll
+    for (int ph = 0; ph < PH * PH; ++ph) {
+      if (phase == ph) {
+        // plain read-add-write (an LDS float atomic costs about 38 clocks per instruction here):
+        // the lanes of a phase touch disjoint pixels, and a lane's own entries are distinct
+        float cur[t][t];
+#pragma unroll
+        for (int a = 0; a < t; ++a)
+#pragma unroll
+          for (int b = 0; b < t; ++b) cur[a][b] = my[at[a][b]];
+#pragma unroll
+        for (int a = 0; a < t; ++a)
+#pragma unroll
+          for (int b = 0; b < t; ++b) my[at[a][b]] = cur[a][b] + d[a][b];
+      }
+      // the next phase adds to what this one wrote: keep the compiler from moving LDS accesses across
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+  }
+  for (int i = 0; i < n_img; ++i) {
+    const float* from = my + (size_t)i * plane;
+    const __amdgpu_buffer_rsrc_t dst =
+        make_rsrc(din + (size_t)(n0 + i) * g.in_image_stride + (size_t)c * plane, (uint32_t)plane * 4u);
+    for (int e0 = 0; e0 < plane; e0 += 64)  // lanes past the plane's end read their wave's padding and store nothing
+      buffer_store_f32<SWCONV_AUX_OUT>(dst, lane * 4u, e0 * 4u, from[min(e0 + lane, plane - 1)]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Eq. 5, second line, last step: the per-tile-block partial sums of every stream entry (written by
 // the sparse kernel in sampled mode) are added over the tile blocks, in ascending order, and go to
 // the entry's place in the caller's CSR order; padding entries (index -1) are skipped.
@@ -198,8 +293,17 @@ __global__ __launch_bounds__(256) void weight_grad_reduce_kernel(const float* __
   if (e >= n_entries) return;
   const int32_t q = entry_index[e];
   if (q < 0) return;
+  // eight loads in flight, added in ascending order of the tile block
   float sum = 0.0f;
-  for (int tb = 0; tb < n_tau_blocks; ++tb) sum += partial[(size_t)tb * partial_stride + e];
+  int tb = 0;
+  for (; tb + 8 <= n_tau_blocks; tb += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(tb + u) * partial_stride + e];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) sum += v[u];
+  }
+  for (; tb < n_tau_blocks; ++tb) sum += partial[(size_t)tb * partial_stride + e];
   dvals[q] = sum;
 }
 

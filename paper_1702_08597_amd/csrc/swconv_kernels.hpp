@@ -362,47 +362,58 @@ __device__ __forceinline__ void quarter_batch(const float* panel, uint32_t lane_
 // ---- sampled mode (backward pass, Eq. 5 second line): dL/dW_F at the stored entries ----
 // The same walk over the packed W_F, but instead of accumulating w * x into the row, every stored
 // entry (k, c) gets the dot product of dL/dZ[p][k][.] with the panel row of c over the 64 tiles of
-// the block: the lane multiplies its four tiles, the 16 lanes of the quarter are summed with four
-// DPP exchanges, and lane i of the quarter keeps the sum of step i, so that after a batch every
+// the block: the lane multiplies its four tiles, the 16 lanes of the quarter are summed with DPP
+// exchanges, and lane i of the quarter ends up with the sum of step i, so that after a batch every
 // lane holds the partial sum of "its" stream entry and the wave stores 256 contiguous bytes.
 
-// Sum over the 16 lanes of a quarter; every lane gets the total.
-__device__ __forceinline__ float quarter_sum(float d) {
-  d += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, d), 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
-  d += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, d), 0x4E, 0xf, 0xf, true));   // quad_perm [2,3,0,1]
-  d += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, d), 0x141, 0xf, 0xf, true));  // row_half_mirror
-  d += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, d), 0x140, 0xf, 0xf, true));  // row_mirror
-  return d;
+// x + (the value of `send` in the lane given by the DPP control): one v_add_f32 with a DPP operand.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x, float send) {
+  return x + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), CTRL, 0xf, 0xf, true));
 }
 
+// Steps G*kStepGroup .. +kStepGroup-1: the lane's share (its four tiles) of each step's dot product.
 template <int G>
 __device__ __forceinline__ void sampled_group(const float* panel, uint32_t lane_sub, uint32_t boff, const f32x4_t& z,
-                                              int lane_in_quarter, float& res) {
+                                              float (&d)[kBatchSteps]) {
   constexpr int I0 = G * kStepGroup;
   const Group4 g = quarter_reads<G>(panel, lane_sub, boff);
   const f32x4_t* x[4] = {&g.x0, &g.x1, &g.x2, &g.x3};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const f32x4_t& v = *x[i];
-    float d = z[0] * v[0];
-    d = fmaf(z[1], v[1], d);
-    d = fmaf(z[2], v[2], d);
-    d = fmaf(z[3], v[3], d);
-    d = quarter_sum(d);
-    res = lane_in_quarter == I0 + i ? d : res;
+    float p = z[0] * v[0];
+    p = fmaf(z[1], v[1], p);
+    p = fmaf(z[2], v[2], p);
+    d[I0 + i] = fmaf(z[3], v[3], p);
   }
 }
 
 // The first `steps` steps of one batch; returns, in lane (q, i), the partial sum of row q, step i
-// (0 for steps that were not run).
+// (0 for steps that were not run).  Every lane first collects its share of all 16 steps; the 16
+// lanes of a quarter then add them up in a transposing butterfly: in the stage with partner
+// lane ^ 15 (then ^ 7, ^ 3, ^ 1: the DPP mirror and quad patterns) a lane keeps the half of its
+// values whose step has the lane's own bit 3 (2, 1, 0) and adds the partner's values for that
+// half, so 8 + 4 + 2 + 1 additions leave the total of step i in lane i - against four additions
+// per step for a reduction step by step.
 __device__ __forceinline__ float sampled_batch(const float* panel, uint32_t lane_sub, const u32x2_t& b, int steps,
                                                const f32x4_t& z, int lane_in_quarter) {
-  float res = 0.0f;
-  sampled_group<0>(panel, lane_sub, b.x, z, lane_in_quarter, res);
-  if (steps > 1 * kStepGroup) sampled_group<1>(panel, lane_sub, b.x, z, lane_in_quarter, res);
-  if (steps > 2 * kStepGroup) sampled_group<2>(panel, lane_sub, b.x, z, lane_in_quarter, res);
-  if (steps > 3 * kStepGroup) sampled_group<3>(panel, lane_sub, b.x, z, lane_in_quarter, res);
-  return res;
+  float d[kBatchSteps];
+#pragma unroll
+  for (int i = 0; i < kBatchSteps; ++i) d[i] = 0.0f;
+  sampled_group<0>(panel, lane_sub, b.x, z, d);
+  if (steps > 1 * kStepGroup) sampled_group<1>(panel, lane_sub, b.x, z, d);
+  if (steps > 2 * kStepGroup) sampled_group<2>(panel, lane_sub, b.x, z, d);
+  if (steps > 3 * kStepGroup) sampled_group<3>(panel, lane_sub, b.x, z, d);
+  const bool b3 = lane_in_quarter & 8, b2 = lane_in_quarter & 4, b1 = lane_in_quarter & 2, b0 = lane_in_quarter & 1;
+  float e[8], f[4], g[2];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) e[i] = dpp_add<0x140>(b3 ? d[i + 8] : d[i], b3 ? d[i] : d[i + 8]);  // row_mirror: lane ^ 15
+#pragma unroll
+  for (int i = 0; i < 4; ++i) f[i] = dpp_add<0x141>(b2 ? e[i + 4] : e[i], b2 ? e[i] : e[i + 4]);  // row_half_mirror: lane ^ 7
+#pragma unroll
+  for (int i = 0; i < 2; ++i) g[i] = dpp_add<0x1B>(b1 ? f[i + 2] : f[i], b1 ? f[i] : f[i + 2]);   // quad_perm [3,2,1,0]: lane ^ 3
+  return dpp_add<0xB1>(b0 ? g[1] : g[0], b0 ? g[0] : g[1]);                                      // quad_perm [1,0,3,2]: lane ^ 1
 }
 
 // SAMPLED = false: Mbuf[p] = A[p] * V[p] (forward step 2; backward Eq. 6 first line on the packed

@@ -132,7 +132,8 @@ def test_backward_can_reuse_the_forward_pass_transform():
         sw.swconv_plan_destroy(plan)
 
 
-def test_profile_backward_reports_seven_kernels_and_skips_unwanted_ones():
+def test_profile_backward_reports_seven_kernels_and_skips_unwanted_ones(monkeypatch):
+    monkeypatch.setenv("SWCONV_FUSE_INPUT_GRAD", "0")   # the seven-kernel pipeline
     N, C, H, W, K, m = 4, 16, 13, 13, 12, 4
     x = synth.activations(N, C, H, W, 1)
     rp, ci, va = synth.bernoulli_weights(36, K, C, 0.3, 2)
@@ -151,6 +152,41 @@ def test_profile_backward_reports_seven_kernels_and_skips_unwanted_ones():
         assert np.all(ms[5:] == 0) and np.all(ms[:5] > 0)
     finally:
         sw.swconv_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("N,C,H,W,K,m,r,pad", [
+    (5, 7, 13, 13, 9, 4, 3, 1),     # four images per wave, a last group of one
+    (3, 6, 13, 13, 5, 2, 3, 1),     # 49 tiles per image: one image per wave
+    (2, 5, 56, 40, 4, 4, 3, 1),     # 140 tiles per image: three passes
+    (3, 5, 27, 27, 6, 2, 5, 2),     # F(2x2,5x5): patches reach two tiles back, stays on two kernels
+    (6, 4, 9, 17, 3, 2, 3, 0),      # no padding
+])
+def test_input_gradient_in_one_kernel_equals_the_two_kernel_path_and_the_oracle(N, C, H, W, K, m, r, pad, monkeypatch):
+    print("input-grad case N=%d C=%d H=%d W=%d K=%d m=%d r=%d" % (N, C, H, W, K, m, r), flush=True)
+    P = (m + r - 1) ** 2
+    Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+    x = synth.activations(N, C, H, W, 9300 + N)
+    rp, ci, va = synth.bernoulli_weights(P, K, C, 0.3, 9301 + K)
+    G = np.random.default_rng(9302).standard_normal((N, K, Ho, Wo)).astype(np.float32)
+    din64, _, _, _ = oracle.backward_f64(x, rp, ci, va, G, K, m, r, pad, want_ZV=False)
+    xd, gd = torch.from_numpy(x).cuda(), torch.from_numpy(G).cuda()
+    got = []
+    for fuse in (1, 0):
+        monkeypatch.setenv("SWCONV_FUSE_INPUT_GRAD", str(fuse))
+        plan = sw.swconv_plan_create(N, C, H, W, K, m, r, pad)
+        try:
+            sw.swconv_set_weights(plan, rp, ci, va)
+            din = torch.full((N, C, H, W), float("nan"), device="cuda")
+            ms = sw.swconv_profile_backward(plan, 0, xd.data_ptr(), gd.data_ptr(), din.data_ptr(), 0, 1)
+            assert (ms[6] == 0) == (fuse == 1 and r == 3) and ms[5] > 0
+            torch.cuda.synchronize()
+            got.append(din.cpu().numpy())
+        finally:
+            sw.swconv_plan_destroy(plan)
+    for d in got:
+        assert not np.isnan(d).any()
+        assert relerr(d, din64) <= RTOL[m]
+    assert relerr(got[0], got[1].astype(np.float64)) <= 1e-5
 
 
 def test_unsupported_K_is_refused():
