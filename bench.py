@@ -96,6 +96,8 @@ def run_backward(args, sw, synth, torch, np, plan, cfg, name, x, xd, rp, ci, va,
         names[5] = "input_grad_kernel"
         models[5] = dict(bytes=4 * (cfg["P"] * cfg["C"] * cfg["T"] + cfg["N"] * cfg["C"] * cfg["H"] * cfg["W"]), flops=0)
     stages = []
+    ran = [i for i in range(len(names)) if stage_ms[i] > 0]     # kernels of the pass that were launched
+    names, models, stage_ms = [names[i] for i in ran], [models[i] for i in ran], stage_ms[ran]
     for nm, ms, mdl in zip(names, stage_ms.tolist(), models):
         gbs = mdl["bytes"] / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
         tfl = mdl["flops"] / (ms * 1e-3) / 1e12 if ms > 0 else 0.0

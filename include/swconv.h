@@ -178,7 +178,10 @@ int swconv_set_weights_device(swconv_plan* plan, void* hip_stream, const int32_t
  * pair of HIP events (as swconv_profile_forward); mean milliseconds per kernel, in launch order:
  *   stage_ms  HOST, 7 floats: dL/dZ transform, input transform (I_F again), sampled products,
  *             reduction to CSR order, transposed sparse product, patch transform, gather;
- *             0 for kernels the call does not run (din_dev or dvals_dev NULL).
+ *             0 for kernels the call does not run (din_dev or dvals_dev NULL).  Where the image
+ *             planes fit LDS (3x3 filters) the last two run as one kernel that keeps no patch
+ *             buffer: the sixth value is its time and the seventh is 0 (the environment
+ *             variable SWCONV_FUSE_INPUT_GRAD=0, read by swconv_plan_create, keeps two kernels).
  * Blocks the host.  Errors as for swconv_backward; EINVAL for iters < 1.
  */
 int swconv_profile_backward(swconv_plan* plan, void* hip_stream, const float* in_dev, const float* dout_dev,
