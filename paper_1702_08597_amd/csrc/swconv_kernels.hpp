@@ -160,6 +160,7 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
   float* my = stage + wave * g.in_area;
   const BlockImage* bi = blocks + (size_t)blockIdx.x * g.slots;
   const size_t plane = (size_t)g.H * g.W;
+  const TileInfo ti = tiles[tau0 + lane];  // asked for first: it arrives while the rows are staged
   if (c < g.C) {
     // Each image part is read through its own buffer descriptor (base = first staged element,
     // size = the part's bytes): lanes past the end read zeros, so loads and LDS writes need no
@@ -198,7 +199,6 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
   if (c >= g.C) return;
   float d[t][t];
   {
-    const TileInfo ti = tiles[tau0 + lane];
     const int y0 = (int16_t)(ti.yx0 & 0xffff), x0 = ti.yx0 >> 16;
     const int y_lo = ti.ylim & 0xffff, y_last = ti.ylim >> 16;
     const float* img = my + ti.in_org;
@@ -614,6 +614,7 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
   const int tau0 = blockIdx.x * 64;
   if (tau0 >= g.T) return;  // whole block is padding (uniform for the block)
   float* my = stage + wave * g.out_area;
+  const TileInfo ti = tiles[tau0 + lane];  // asked for before the t*t loads below, used after them
   if (k < g.K) {
     const __amdgpu_buffer_rsrc_t mr = make_rsrc(Mbuf, g.m_bytes);
     const uint32_t row0 = ((uint32_t)k * g.Tp + tau0) * 4u;        // wave-uniform byte offset, position 0
@@ -630,7 +631,6 @@ __global__ __launch_bounds__(256) void output_transform_kernel(const float* __re
       }
     float y[M][M];
     output_transform<M, R>(z, y);
-    const TileInfo ti = tiles[tau0 + lane];
     const int y0 = (int16_t)(ti.yx0 & 0xffff), x0 = ti.yx0 >> 16;
     // rows / columns of the tile inside the output (<= 0 for a padding tile, whose y0 is -32768)
     const int rows = y0 == -32768 ? 0 : g.Ho - (y0 + g.pad), cols = g.Wo - (x0 + g.pad);
