@@ -237,3 +237,41 @@ def test_profile_forward_returns_positive_stage_times_and_same_output():
         np.testing.assert_array_equal(L.out.cpu().numpy(), ref)
     finally:
         L.close()
+
+
+def test_workspaces_just_below_the_4_gib_offset_limit_on_sampled_images():
+    # V and M are addressed with 32-bit byte offsets; this plan's workspaces are 4.13e9 bytes each
+    # (2**32 = 4.29e9).  The layer treats images independently, so the oracle checks the first, a
+    # middle and the last images - the last ones sit at the top of the offset range.
+    N, C, H, W, K, m = 28000, 64, 13, 13, 64, 4
+    P, T, Ho, Wo = 36, N * 16, 13, 13
+    assert 36 * 64 * T * 4 > 0.96 * 2 ** 32
+    plan = sw.swconv_plan_create(N, C, H, W, K, m, 3, 1)
+    try:
+        assert sw.swconv_plan_sizes(plan) == (P, T, Ho, Wo)
+        rp, ci, va = synth.bernoulli_weights(P, K, C, 0.2, 4401)
+        sw.swconv_set_weights(plan, rp, ci, va)
+        gen = torch.Generator(device="cuda").manual_seed(4402)
+        xd = torch.randn((N, C, H, W), device="cuda", generator=gen).clamp_(min=0)
+        gd = torch.randn((N, K, Ho, Wo), device="cuda", generator=gen)
+        out = torch.full((N, K, Ho, Wo), float("nan"), device="cuda")
+        din = torch.full((N, C, H, W), float("nan"), device="cuda")
+        print("forward", flush=True)
+        sw.swconv_forward(plan, 0, xd.data_ptr(), out.data_ptr())
+        torch.cuda.synchronize()
+        print("backward", flush=True)
+        sw.swconv_backward(plan, 0, xd.data_ptr(), gd.data_ptr(), din.data_ptr(), 0)
+        torch.cuda.synchronize()
+        assert not torch.isnan(out).any().item() and not torch.isnan(din).any().item()
+        for n0 in (0, 13999, N - 3):
+            xs, gs = xd[n0:n0 + 3].cpu().numpy(), gd[n0:n0 + 3].cpu().numpy()
+            o64, _, _ = oracle.forward_f64(xs, rp, ci, va, K, m, 3, 1, want_VM=False)
+            din64, _, _, _ = oracle.backward_f64(xs, rp, ci, va, gs, K, m, 3, 1, want_ZV=False)
+            assert relerr(out[n0:n0 + 3].cpu().numpy(), o64) <= RTOL[m]
+            assert relerr(din[n0:n0 + 3].cpu().numpy(), din64) <= RTOL[m]
+    finally:
+        sw.swconv_plan_destroy(plan)
+    # one more image row of tiles and the plan is refused, not wrapped around
+    with pytest.raises(sw.SwconvError) as e:
+        sw.swconv_plan_create(30000, C, H, W, K, m, 3, 1)
+    assert e.value.status == sw.SWCONV_EUNSUPPORTED
