@@ -21,6 +21,15 @@ def dense_csr(P, K, C):
     return rowptr, np.tile(np.arange(C, dtype=np.int32), P * K)
 
 
+def test_matrices_match_the_hand_typed_fixture():
+    from test_oracle_pins import load_golden_matrices
+    gold = load_golden_matrices()[(2, 5)]
+    AT, BT, G = oracle.winograd_matrices(M, R)
+    np.testing.assert_array_equal(AT, gold["AT"])
+    np.testing.assert_array_equal(BT, gold["BT"])
+    np.testing.assert_array_equal(G, gold["G"])
+
+
 def test_matrices_are_the_vandermonde_construction_on_the_f43_points():
     AT, BT, G = oracle.winograd_matrices(M, R)
     assert AT.shape == (2, 6) and BT.shape == (6, 6) and G.shape == (6, 5)
