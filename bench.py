@@ -24,7 +24,7 @@ STAGES = ("input_transform_kernel", "spmm_kernel", "output_transform_kernel")
 # HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain
 # copy of known size (profiles/pmc_traffic_alexnet_conv3_n32_f4.md); known for the default workload only.
 MEASURED_TRAFFIC = {
-    ("alexnet_conv3_n32_f4", 0.10): {"input_transform_kernel": 24.51e6, "spmm_kernel": 52.02e6,
+    ("alexnet_conv3_n32_f4", 0.10): {"input_transform_kernel": 24.51e6, "spmm_kernel": 51.77e6,
                                      "output_transform_kernel": 37.72e6},
 }
 
