@@ -171,8 +171,9 @@ __global__ __launch_bounds__(kFusedWaves * 64) void product_output_kernel(
     const uint32_t pair = cols > 1 ? at : kParked, single = cols == 1 ? at : kParked;
     buffer_store_f32x2<SWCONV_AUX_OUT>(orr, rows > 0 ? pair : kParked, 0u, v00, v01);
     buffer_store_f32<SWCONV_AUX_OUT>(orr, rows > 0 ? single : kParked, 0u, v00);
-    buffer_store_f32x2<SWCONV_AUX_OUT>(orr, rows > 1 ? pair : kParked, (uint32_t)Wo * 4u, v10, v11);
-    buffer_store_f32<SWCONV_AUX_OUT>(orr, rows > 1 ? single : kParked, (uint32_t)Wo * 4u, v10);
+    const uint32_t below = (uint32_t)Wo * 4u;  // added to live offsets only: a parked one must not wrap around
+    buffer_store_f32x2<SWCONV_AUX_OUT>(orr, rows > 1 && cols > 1 ? at + below : kParked, 0u, v10, v11);
+    buffer_store_f32<SWCONV_AUX_OUT>(orr, rows > 1 && cols == 1 ? at + below : kParked, 0u, v10);
   };
   store_tile(o0, y00.a0, y01.a0, y10.a0, y11.a0);
   store_tile(o1, y00.a1, y01.a1, y10.a1, y11.a1);
