@@ -275,3 +275,27 @@ def test_workspaces_just_below_the_4_gib_offset_limit_on_sampled_images():
     with pytest.raises(sw.SwconvError) as e:
         sw.swconv_plan_create(30000, C, H, W, K, m, 3, 1)
     assert e.value.status == sw.SWCONV_EUNSUPPORTED
+
+
+def test_schedule_settings_do_not_change_a_single_bit(monkeypatch):
+    # how the work is cut into ranges decides who computes a row, not how the row is summed
+    N, C, H, W, K, m = 9, 40, 13, 13, 70, 4
+    x = synth.activations(N, C, H, W, 5101)
+    rp, ci, va = synth.skewed_weights(36, K, C, 5102)
+    outs = []
+    for env in ({}, {"SWCONV_SPMM_WGS": "37"}, {"SWCONV_SPMM_SECOND_SHARE": "40"},
+                {"SWCONV_SPMM_WAVES": "8", "SWCONV_SPMM_WGS": "301", "SWCONV_SPMM_SLICE_COST": "5"}):
+        with monkeypatch.context() as mp:
+            for k, v in env.items():
+                mp.setenv(k, v)
+            L = GpuLayer(N, C, H, W, K, m)
+            try:
+                L.set_weights(rp, ci, va)
+                sw.swconv_debug_check_schedule(L.plan)
+                outs.append(L.forward(x).copy())
+            finally:
+                L.close()
+    for o in outs[1:]:
+        np.testing.assert_array_equal(o.view(np.uint32), outs[0].view(np.uint32))
+    o64, _, _ = oracle.forward_f64(x, rp, ci, va, K, m, 3, 1, want_VM=False)
+    assert relerr(outs[0], o64) <= RTOL[m]

@@ -164,3 +164,32 @@ def test_schedule_is_a_partition(N, C, H, W, K, m, density):
     assert sw.swconv_set_weights_status(pl, rp, ci, va) in (sw.SWCONV_OK, sw.SWCONV_EHIP)
     sw.swconv_debug_check_schedule(pl)
     sw.swconv_plan_destroy(pl)
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("env", [{}, {"SWCONV_SPMM_SECOND_SHARE": "40"}, {"SWCONV_SPMM_WGS": "37"},
+                                 {"SWCONV_SPMM_WGS": "301", "SWCONV_SPMM_SECOND_SHARE": "55", "SWCONV_SPMM_WAVES": "8"}])
+def test_schedule_is_a_partition_for_random_shapes_and_cost_settings(seed, env, monkeypatch):
+    # the cut into ranges (budgets that depend on where a range's workgroup sits, the re-cut when
+    # fewer workgroups are used than assumed) must hand out every (position, tile block, slice) once
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    rng = np.random.default_rng(9000 + seed)
+    for _ in range(4):
+        m, r = [(2, 3), (4, 3), (2, 5)][int(rng.integers(0, 3))]
+        N, C, K = int(rng.integers(1, 70)), int(rng.integers(1, 400)), int(rng.integers(1, 500))
+        H, W = int(rng.integers(r, 30)), int(rng.integers(r, 30))
+        P = (m + r - 1) ** 2
+        pl = sw.swconv_plan_create(N, C, H, W, K, m, r, r // 2)
+        if rng.random() < 0.3:
+            rp, ci, va = synth.skewed_weights(P, K, C, int(rng.integers(1 << 30)))
+        else:
+            rp, ci, va = synth.bernoulli_weights(P, K, C, float(rng.choice([0.0, 0.02, 0.1, 0.5, 1.0])),
+                                                 int(rng.integers(1 << 30)))
+        assert sw.swconv_set_weights_status(pl, rp, ci, va) in (sw.SWCONV_OK, sw.SWCONV_EHIP)
+        sw.swconv_debug_check_schedule(pl)
+        rp2, ci2, va2 = sw.swconv_debug_export_weights(pl, K, int(rp[-1]))
+        np.testing.assert_array_equal(rp2, rp)
+        np.testing.assert_array_equal(ci2, ci)
+        np.testing.assert_array_equal(va2.view(np.uint32), va.view(np.uint32))
+        sw.swconv_plan_destroy(pl)
