@@ -254,7 +254,15 @@ __global__ __launch_bounds__(256) void input_grad_kernel(const float* __restrict
     }
 #pragma unroll
     for (int ph = 0; ph < PH * PH; ++ph) {
-      if (phase == ph) {
+      if (ph == 0 && base == tau0) {
+        // first phase of the first pass: the planes still hold zeros, so the patch is stored as it is
+        if (phase == 0) {
+#pragma unroll
+          for (int a = 0; a < t; ++a)
+#pragma unroll
+            for (int b = 0; b < t; ++b) my[at[a][b]] = d[a][b];
+        }
+      } else if (phase == ph) {
         // plain read-add-write (an LDS float atomic costs about 38 clocks per instruction here):
         // the lanes of a phase touch disjoint pixels, and a lane's own entries are distinct
         float cur[t][t];
