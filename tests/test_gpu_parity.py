@@ -299,3 +299,44 @@ def test_schedule_settings_do_not_change_a_single_bit(monkeypatch):
         np.testing.assert_array_equal(o.view(np.uint32), outs[0].view(np.uint32))
     o64, _, _ = oracle.forward_f64(x, rp, ci, va, K, m, 3, 1, want_VM=False)
     assert relerr(outs[0], o64) <= RTOL[m]
+
+
+def test_two_plans_on_two_streams_at_once():
+    # plans own their workspaces and schedules; nothing is shared between them, so two layers
+    # may be in flight together (forward and backward), each on a stream of its own
+    shapes = [(6, 24, 13, 13, 20, 4, 3, 1), (4, 12, 27, 27, 16, 2, 5, 2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    jobs = []
+    for (N, C, H, W, K, m, r, pad), st in zip(shapes, streams):
+        P = (m + r - 1) ** 2
+        Ho, Wo = H + 2 * pad - r + 1, W + 2 * pad - r + 1
+        x = synth.activations(N, C, H, W, 6100 + C)
+        rp, ci, va = synth.bernoulli_weights(P, K, C, 0.3, 6200 + K)
+        G = np.random.default_rng(6300 + K).standard_normal((N, K, Ho, Wo)).astype(np.float32)
+        plan = sw.swconv_plan_create(N, C, H, W, K, m, r, pad)
+        sw.swconv_set_weights(plan, rp, ci, va)
+        jobs.append(dict(plan=plan, st=st, x=x, rp=rp, ci=ci, va=va, G=G, K=K, m=m, r=r, pad=pad,
+                         xd=torch.from_numpy(x).cuda(), gd=torch.from_numpy(G).cuda(),
+                         out=torch.full((N, K, Ho, Wo), float("nan"), device="cuda"),
+                         din=torch.full((N, C, H, W), float("nan"), device="cuda"),
+                         dv=torch.full((len(va),), float("nan"), device="cuda")))
+    torch.cuda.synchronize()
+    try:
+        for rep in range(3):                      # interleaved launches, no synchronisation in between
+            for j in jobs:
+                sw.swconv_forward(j["plan"], j["st"].cuda_stream, j["xd"].data_ptr(), j["out"].data_ptr())
+            for j in jobs:
+                sw.swconv_backward(j["plan"], j["st"].cuda_stream, j["xd"].data_ptr(), j["gd"].data_ptr(),
+                                   j["din"].data_ptr(), j["dv"].data_ptr())
+        torch.cuda.synchronize()
+        for j in jobs:
+            tol = 1e-4
+            o64, _, _ = oracle.forward_f64(j["x"], j["rp"], j["ci"], j["va"], j["K"], j["m"], j["r"], j["pad"], want_VM=False)
+            din64, dv64, _, _ = oracle.backward_f64(j["x"], j["rp"], j["ci"], j["va"], j["G"], j["K"], j["m"], j["r"],
+                                                    j["pad"], want_ZV=False)
+            assert relerr(j["out"].cpu().numpy(), o64) <= tol
+            assert relerr(j["din"].cpu().numpy(), din64) <= tol
+            assert relerr(j["dv"].cpu().numpy(), dv64) <= tol
+    finally:
+        for j in jobs:
+            sw.swconv_plan_destroy(j["plan"])
