@@ -106,7 +106,10 @@ int swconv_set_weights(swconv_plan* plan, const int32_t* rowptr, const int32_t* 
  *   in_dev   DEVICE, N x C x H x W fp32, contiguous (W fastest), read-only.
  *   out_dev  DEVICE, N x K x Ho x Wo fp32, contiguous; every element is overwritten.
  * The two must not alias and must live on the device the weights were set on.  The plan owns
- * the V and M workspaces, so one plan must not run on two streams at once.
+ * the V and M workspaces, so one plan must not run on two streams at once.  The call allocates
+ * nothing and enqueues kernels only: after one eager call (which sets kernel attributes once per
+ * process) it may be recorded into a HIP graph; the same holds for swconv_backward once one eager
+ * backward pass has packed the transposed weights.
  * Errors: EINVAL (null), ESTATE (no weights), EHIP (launch failure).
  */
 int swconv_forward(swconv_plan* plan, void* hip_stream, const float* in_dev, float* out_dev);

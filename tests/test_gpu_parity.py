@@ -340,3 +340,43 @@ def test_two_plans_on_two_streams_at_once():
     finally:
         for j in jobs:
             sw.swconv_plan_destroy(j["plan"])
+
+
+def test_forward_and_backward_replay_from_a_hip_graph():
+    # the passes only launch kernels (no allocation, no memset), so a caller may capture them;
+    # every replay must give what the eager call gives, bit for bit, with fresh inputs each time
+    N, C, H, W, K, m = 6, 32, 13, 13, 24, 4
+    rp, ci, va = synth.bernoulli_weights(36, K, C, 0.3, 7001)
+    plan = sw.swconv_plan_create(N, C, H, W, K, m, 3, 1)
+    try:
+        sw.swconv_set_weights(plan, rp, ci, va)
+        xs = [torch.from_numpy(synth.activations(N, C, H, W, 7100 + i)).cuda() for i in range(3)]
+        gs = [torch.randn((N, K, 13, 13), device="cuda", generator=torch.Generator(device="cuda").manual_seed(7200 + i))
+              for i in range(3)]
+        x_in, g_in = torch.empty_like(xs[0]), torch.empty_like(gs[0])
+        out, din = torch.empty((N, K, 13, 13), device="cuda"), torch.empty((N, C, H, W), device="cuda")
+        dv = torch.empty((len(va),), device="cuda")
+
+        def passes(stream):
+            sw.swconv_forward(plan, stream, x_in.data_ptr(), out.data_ptr())
+            sw.swconv_backward(plan, stream, 0, g_in.data_ptr(), din.data_ptr(), dv.data_ptr())   # reuses I_F
+
+        eager = []
+        for x, g in zip(xs, gs):        # also the warm-up: first-call set-up happens outside the capture
+            x_in.copy_(x); g_in.copy_(g)
+            passes(torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            eager.append((out.clone(), din.clone(), dv.clone()))
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            passes(torch.cuda.current_stream().cuda_stream)
+        for rep in range(2):
+            for (x, g), want in zip(zip(xs, gs), eager):
+                x_in.copy_(x); g_in.copy_(g)
+                out.fill_(float("nan")); din.fill_(float("nan")); dv.fill_(float("nan"))
+                graph.replay()
+                torch.cuda.synchronize()
+                for got, ref in zip((out, din, dv), want):
+                    assert torch.equal(got.view(torch.int32), ref.view(torch.int32))
+    finally:
+        sw.swconv_plan_destroy(plan)
