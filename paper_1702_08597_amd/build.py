@@ -13,7 +13,7 @@ HEADERS.append(os.path.join(os.path.dirname(HERE), "include", "swconv.h"))
 
 # -packed-fp32-ops: keep hipcc from forming packed fp32 VALU instructions (the host pass prints a
 # harmless "not a recognized feature" warning for it).
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

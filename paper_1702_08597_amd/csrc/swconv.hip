@@ -9,7 +9,9 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <atomic>
 #include <numeric>
+#include <thread>
 #include <type_traits>
 #include <vector>
 
@@ -34,6 +36,32 @@ int env_int(const char* name, int dflt) {
   return (end && *end == 0) ? (int)v : dflt;
 }
 
+// Host threads for the re-packing of the weights (a plan's set_weights is a few milliseconds of
+// host work on a pruned AlexNet layer; a training loop that prunes every step calls it every step).
+int host_threads() {
+  const int hw = (int)std::thread::hardware_concurrency();
+  return std::max(1, std::min(16, env_int("SWCONV_HOST_THREADS", hw > 0 ? hw : 1)));
+}
+
+// f(i) for every i in [0, n), the indices handed out by a shared counter to up to host_threads()
+// threads (the caller's included).  f must not throw.  Threads that cannot be started are done without.
+template <typename F>
+void parallel_for(int n, F&& f) {
+  const int nt = std::min(n, host_threads());
+  std::atomic<int> next{0};
+  auto work = [&]() {
+    for (int i = next.fetch_add(1, std::memory_order_relaxed); i < n; i = next.fetch_add(1, std::memory_order_relaxed)) f(i);
+  };
+  std::vector<std::thread> helpers;
+  try {
+    helpers.reserve((size_t)std::max(0, nt - 1));
+    for (int t = 1; t < nt; ++t) helpers.emplace_back(work);
+  } catch (...) {
+  }
+  work();
+  for (std::thread& t : helpers) t.join();
+}
+
 #define HIP_TRY(expr)                         \
   do {                                        \
     hipError_t e_ = (expr);                   \
@@ -43,14 +71,23 @@ int env_int(const char* name, int dflt) {
     }                                         \
   } while (0)
 
+// Copy h to the device.  With `cap` (the bytes *dptr holds, kept by the caller) the allocation is kept
+// while it is large enough: a weight update then costs copies only.  The caller makes sure no kernel
+// still reads the old contents.
 template <typename T>
-int upload(T** dptr, const std::vector<T>& h) {
+int upload(T** dptr, const std::vector<T>& h, size_t* cap = nullptr) {
+  const size_t bytes = std::max<size_t>(h.size(), 1) * sizeof(T);
+  if (cap && *dptr && *cap >= bytes) {
+    if (!h.empty()) HIP_TRY(hipMemcpy(*dptr, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice));
+    return SWCONV_OK;
+  }
   if (*dptr) {
     (void)hipFree(*dptr);
     *dptr = nullptr;
   }
-  const size_t bytes = std::max<size_t>(h.size(), 1) * sizeof(T);
+  if (cap) *cap = 0;
   HIP_TRY(hipMalloc((void**)dptr, bytes));
+  if (cap) *cap = bytes;
   if (!h.empty()) HIP_TRY(hipMemcpy(*dptr, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice));
   return SWCONV_OK;
 }
@@ -82,6 +119,7 @@ struct PackedMatrix {
   Slice* d_slices = nullptr;
   WorkItem* d_items = nullptr;
   RangeHeader* d_ranges = nullptr;
+  size_t cap_stream = 0, cap_slices = 0, cap_items = 0, cap_ranges = 0;  // bytes of the four allocations
 };
 
 // W_F packed for the fused product + output transform kernel (m = 2, few input channels): rows in
@@ -97,6 +135,7 @@ struct FusedProduct {
   uint32_t* d_wpk = nullptr;
   uint8_t* d_lens = nullptr;
   OutTile* d_otiles = nullptr;
+  size_t cap_wpk = 0, cap_lens = 0;
 };
 
 struct swconv_plan {
@@ -128,6 +167,7 @@ struct swconv_plan {
   float* d_partial = nullptr; // backward pass: [tile blocks][stream entries of W_F] partial dot products
   size_t partial_floats = 0;
   int32_t* d_entry_index = nullptr;
+  size_t cap_entry_index = 0;
   bool index_current = false;
   bool ran_backward = false;
   float* d_wdense = nullptr;  // [P][C][Kq]
@@ -384,8 +424,8 @@ int upload_fused(swconv_plan* pl) {
   if (!fz.ready) return SWCONV_OK;
   fz.ready = false;
   int rc;
-  if ((rc = upload(&fz.d_wpk, fz.wpk))) return rc;
-  if ((rc = upload(&fz.d_lens, fz.lens))) return rc;
+  if ((rc = upload(&fz.d_wpk, fz.wpk, &fz.cap_wpk))) return rc;
+  if ((rc = upload(&fz.d_lens, fz.lens, &fz.cap_lens))) return rc;
   if (!fz.d_otiles && (rc = upload(&fz.d_otiles, fz.otiles))) return rc;
   HIP_TRY(hipDeviceSynchronize());
   fz.ready = true;
@@ -400,16 +440,22 @@ int validate_csr(const swconv_plan* pl, const int32_t* rowptr, const int32_t* co
     if (rowptr[i + 1] < rowptr[i]) return SWCONV_EINVAL;
   const int64_t nnz = rowptr[rows];
   if (nnz > 0 && (!colidx || !vals)) return SWCONV_EINVAL;
-  for (int64_t i = 0; i < rows; ++i) {
-    if (rowptr[i + 1] - rowptr[i] > pl->g.C) return SWCONV_EINVAL;
-    int32_t prev = -1;
-    for (int32_t q = rowptr[i]; q < rowptr[i + 1]; ++q) {
-      const int32_t c = colidx[q];
-      if (c <= prev || c >= pl->g.C) return SWCONV_EINVAL;
-      prev = c;
+  const int C = pl->g.C;
+  constexpr int64_t kChunk = 1024;  // rows per unit of work
+  std::atomic<bool> bad{false};
+  parallel_for((int)((rows + kChunk - 1) / kChunk), [&](int chunk) {
+    const int64_t end = std::min(rows, (int64_t)(chunk + 1) * kChunk);
+    for (int64_t i = (int64_t)chunk * kChunk; i < end; ++i) {
+      if (rowptr[i + 1] - rowptr[i] > C) bad.store(true, std::memory_order_relaxed);
+      int32_t prev = -1;
+      for (int32_t q = rowptr[i]; q < rowptr[i + 1]; ++q) {
+        const int32_t c = colidx[q];
+        if (c <= prev || c >= C) bad.store(true, std::memory_order_relaxed);
+        prev = c;
+      }
     }
-  }
-  return SWCONV_OK;
+  });
+  return bad.load() ? SWCONV_EINVAL : SWCONV_OK;
 }
 
 // Static schedule of the sparse product.  The units (position, tile block, slice), in that order,
@@ -452,6 +498,9 @@ void build_schedule(PackedMatrix* pm, int P, int ntb) {
     return second ? std::max(floor_budget, budget * second_share / 100) : budget;
   };
 
+  std::vector<int64_t> cost_before(pm->slices.size() + 1, 0);
+  for (size_t i = 0; i < pm->slices.size(); ++i) cost_before[i + 1] = cost_before[i] + pm->slices[i].len + slice_ovh;
+
   auto cut = [&](int64_t base_budget, std::vector<WorkItem>* items, std::vector<int32_t>* begin) -> int {
     int wgs = 0;
     int64_t acc = 0;
@@ -476,12 +525,14 @@ void build_schedule(PackedMatrix* pm, int P, int ntb) {
           open_wg = true;
           acc += panel_cost;
           const int s0 = s;
-          while (s < s_end && s - s0 < pm->item_cap) {
-            const int64_t c = pm->slices[s].len + slice_ovh;
-            if (s > s0 && acc + c > budget) break;
-            acc += c;
-            ++s;
-          }
+          // the first slice in any case, then as many as the budget holds (prefix sums of the slice
+          // costs: `cost_before[i]` = cost of all slices before slice i), at most item_cap and the position's
+          const int limit = std::min(s_end, s0 + pm->item_cap);
+          const int64_t room = cost_before[s0] + (budget - acc);
+          s = (int)(std::upper_bound(cost_before.begin() + s0 + 1, cost_before.begin() + limit + 1, room) -
+                    cost_before.begin()) - 1;
+          s = std::max(s, s0 + 1);
+          acc += cost_before[s] - cost_before[s0];
           if (items) items->push_back(WorkItem{p, tb, s0, s});
           if (s < s_end && s - s0 < pm->item_cap) close_wg();  // the budget, not the item cap, ended the item
         }
@@ -580,14 +631,13 @@ void pack_matrix(PackedMatrix* pm, int P, int ntb, const int32_t* rowptr, const 
   pm->sorted_len.assign((size_t)P * Rp, 0);
   pm->slices.assign((size_t)P * slices_per_pos, Slice{});
 
-  std::vector<int32_t> order(R);
-  uint64_t cursor = 0;  // 512-byte batches
-  pm->padded_nnz = 0;
-  for (int p = 0; p < P; ++p) {
+  // per position (in parallel): rows sorted by length, four to a slice
+  std::vector<int32_t> order_all((size_t)P * R);
+  parallel_for(P, [&](int p) {
     const int32_t* rp = rowptr + (int64_t)p * R;
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(),
-                     [&](int32_t a, int32_t b) { return rp[a + 1] - rp[a] > rp[b + 1] - rp[b]; });
+    int32_t* order = order_all.data() + (size_t)p * R;
+    std::iota(order, order + R, 0);
+    std::stable_sort(order, order + R, [&](int32_t a, int32_t b) { return rp[a + 1] - rp[a] > rp[b + 1] - rp[b]; });
     for (int i = 0; i < R; ++i) {
       pm->sorted_rows[(size_t)p * Rp + i] = order[i];
       pm->sorted_len[(size_t)p * Rp + i] = rp[order[i] + 1] - rp[order[i]];
@@ -596,37 +646,59 @@ void pack_matrix(PackedMatrix* pm, int P, int ntb, const int32_t* rowptr, const 
       Slice& sl = pm->slices[(size_t)p * slices_per_pos + s];
       sl.p = p;
       sl.row0 = p * Rp + s * kSliceRows;
-      sl.batch0 = (uint32_t)cursor;
       for (int r = 0; r < kSliceRows; ++r) sl.k[r] = pm->sorted_rows[sl.row0 + r];
       // rows are sorted: the first is the longest; whole groups of steps
       sl.len = (pm->sorted_len[sl.row0] + kStepGroup - 1) / kStepGroup * kStepGroup;
-      cursor += (sl.len + kBatchSteps - 1) / kBatchSteps;
-      pm->padded_nnz += (int64_t)sl.len * kSliceRows;
     }
+  });
+  // where each slice's batches start in the stream
+  uint64_t cursor = 0;  // 512-byte batches
+  pm->padded_nnz = 0;
+  for (Slice& sl : pm->slices) {
+    sl.batch0 = (uint32_t)cursor;
+    cursor += (sl.len + kBatchSteps - 1) / kBatchSteps;
+    pm->padded_nnz += (int64_t)sl.len * kSliceRows;
   }
   // an entry is (byte offset of the panel row of its column, weight); padding = row 0, weight +0.0f.
   // The kernel addresses the stream with 32-bit byte offsets and fetches up to two batches past a
   // slice's end: two spare batches keep even those inside the allocation.
+  const uint64_t spare0 = cursor;
   cursor += 2;
   if (cursor * 512 >= ((uint64_t)1 << 32) - 4096) throw std::bad_alloc();
   const uint32_t row_bytes = (uint32_t)kTileBlock * sizeof(float);
-  pm->stream.assign((size_t)cursor * 128, 0u);
-  pm->entry_index.assign((size_t)cursor * 64, -1);
-  for (size_t s = 0; s < pm->slices.size(); ++s) {
-    const Slice& sl = pm->slices[s];
-    const int32_t* rp = rowptr + (int64_t)sl.p * R;
-    for (int r = 0; r < kSliceRows; ++r) {
-      const int row = pm->sorted_rows[sl.row0 + r];
-      if (row < 0) continue;
-      const int32_t q0 = rp[row], len = rp[row + 1] - rp[row];
-      for (int32_t e = 0; e < len; ++e) {
-        uint32_t* entry = &pm->stream[stream_entry(sl.batch0, r, e)];
-        entry[0] = (uint32_t)colidx[q0 + e] * row_bytes;
-        std::memcpy(&entry[1], &vals[q0 + e], sizeof(float));
-        pm->entry_index[stream_entry(sl.batch0, r, e) / 2] = q0 + e;
+  pm->stream.resize((size_t)cursor * 128);
+  pm->entry_index.resize((size_t)cursor * 64);
+  std::fill(pm->stream.begin() + (size_t)spare0 * 128, pm->stream.end(), 0u);
+  std::fill(pm->entry_index.begin() + (size_t)spare0 * 64, pm->entry_index.end(), -1);
+  // per position (in parallel): every pair of every batch of its slices is written once, entry or padding
+  parallel_for(P, [&](int p) {
+    const int32_t* rp = rowptr + (int64_t)p * R;
+    for (int s = 0; s < slices_per_pos; ++s) {
+      const Slice& sl = pm->slices[(size_t)p * slices_per_pos + s];
+      const int batches = (sl.len + kBatchSteps - 1) / kBatchSteps;
+      for (int r = 0; r < kSliceRows; ++r) {
+        const int row = pm->sorted_rows[sl.row0 + r];
+        const int32_t q0 = row < 0 ? 0 : rp[row], len = row < 0 ? 0 : rp[row + 1] - rp[row];
+        for (int b = 0; b < batches; ++b) {
+          const size_t first = stream_entry(sl.batch0, r, b * kBatchSteps);  // the row's 16 pairs of a batch are contiguous
+          uint32_t* entry = &pm->stream[first];
+          int32_t* index = &pm->entry_index[first / 2];
+          for (int i = 0; i < kBatchSteps; ++i) {
+            const int32_t e = b * kBatchSteps + i;
+            if (e < len) {
+              entry[2 * i] = (uint32_t)colidx[q0 + e] * row_bytes;
+              std::memcpy(&entry[2 * i + 1], &vals[q0 + e], sizeof(float));
+              index[i] = q0 + e;
+            } else {
+              entry[2 * i] = 0u;
+              entry[2 * i + 1] = 0u;
+              index[i] = -1;
+            }
+          }
+        }
       }
     }
-  }
+  });
   build_schedule(pm, P, ntb);
   pm->packed = true;
 }
@@ -658,10 +730,11 @@ void unpack_matrix(const PackedMatrix& pm, int P, int32_t* rowptr, int32_t* coli
 int upload_packed(PackedMatrix* pm) {
   int rc;
   pm->on_device = false;
-  if ((rc = upload(&pm->d_stream, pm->stream))) return rc;
-  if ((rc = upload(&pm->d_slices, pm->slices))) return rc;
-  if ((rc = upload(&pm->d_items, pm->items))) return rc;
-  if ((rc = upload(&pm->d_ranges, pm->ranges))) return rc;
+  HIP_TRY(hipDeviceSynchronize());  // a pass still in flight may read the buffers that are overwritten below
+  if ((rc = upload(&pm->d_stream, pm->stream, &pm->cap_stream))) return rc;
+  if ((rc = upload(&pm->d_slices, pm->slices, &pm->cap_slices))) return rc;
+  if ((rc = upload(&pm->d_items, pm->items, &pm->cap_items))) return rc;
+  if ((rc = upload(&pm->d_ranges, pm->ranges, &pm->cap_ranges))) return rc;
   HIP_TRY(hipDeviceSynchronize());
   pm->on_device = true;
   return SWCONV_OK;
@@ -675,6 +748,7 @@ void free_packed(PackedMatrix* pm) {
   pm->d_slices = nullptr;
   pm->d_items = nullptr;
   pm->d_ranges = nullptr;
+  pm->cap_stream = pm->cap_slices = pm->cap_items = pm->cap_ranges = 0;
   pm->on_device = false;
 }
 
@@ -760,7 +834,8 @@ int prepare_weight_grad(swconv_plan* pl) {
     pl->partial_floats = need;
   }
   if (!pl->index_current) {
-    int rc = upload(&pl->d_entry_index, pl->fw.entry_index);
+    HIP_TRY(hipDeviceSynchronize());  // an earlier backward pass may still read the index
+    int rc = upload(&pl->d_entry_index, pl->fw.entry_index, &pl->cap_entry_index);
     if (rc) return rc;
     HIP_TRY(hipDeviceSynchronize());
     pl->index_current = true;
