@@ -57,11 +57,13 @@
 
 namespace {
 
+constexpr int kMaxT = 8;  // largest transformed tile: F(4,5)
+
 struct WinogradMatrices {
   int m, r, t;
-  double AT[4][6];  // m x t   (A^T)
-  double BT[6][6];  // t x t   (B^T)
-  double G[6][5];   // t x r
+  double AT[4][kMaxT];      // m x t   (A^T)
+  double BT[kMaxT][kMaxT];  // t x t   (B^T)
+  double G[kMaxT][5];       // t x r
 };
 
 bool winograd_matrices(int m, int r, WinogradMatrices* w) {
@@ -124,6 +126,38 @@ bool winograd_matrices(int m, int r, WinogradMatrices* w) {
     w->AT[1][5] = 1;
     return true;
   }
+  if (m == 4 && r == 5) {
+    // F(4,5), t = 8: the Toom-Cook construction on the points {0, 1, -1, 2, -2, 1/2, -1/2, inf}.
+    // Row i of B^T holds the coefficients (ascending powers) of prod_{k != i} (x - p_k), the row of
+    // the point at infinity those of prod_k (x - p_k); A^T[a][i] = p_i^a with the point at infinity
+    // in the row of the highest power; G[i][j] = p_i^j / prod_{k != i} (p_i - p_k), last row e_4.
+    // All entries of A^T and B^T are dyadic rationals, exact in binary floating point.
+    const double BT[8][8] = {{-1, 0, 5.25, 0, -5.25, 0, 1, 0},
+                             {0, 1, 1, -4.25, -4.25, 1, 1, 0},
+                             {0, -1, 1, 4.25, -4.25, -1, 1, 0},
+                             {0, 0.5, 0.25, -2.5, -1.25, 2, 1, 0},
+                             {0, -0.5, 0.25, 2.5, -1.25, -2, 1, 0},
+                             {0, 2, 4, -2.5, -5, 0.5, 1, 0},
+                             {0, -2, 4, 2.5, -5, -0.5, 1, 0},
+                             {0, -1, 0, 5.25, 0, -5.25, 0, 1}};
+    const double p[7] = {0, 1, -1, 2, -2, 0.5, -0.5};
+    for (int i = 0; i < 8; ++i)
+      for (int j = 0; j < 8; ++j) w->BT[i][j] = BT[i][j];
+    for (int i = 0; i < 7; ++i) {
+      double norm = 1;
+      for (int k = 0; k < 7; ++k)
+        if (k != i) norm *= p[i] - p[k];
+      double pw = 1;
+      for (int j = 0; j < 5; ++j) {
+        w->G[i][j] = pw / norm;
+        if (j < 4) w->AT[j][i] = pw;
+        pw *= p[i];
+      }
+    }
+    w->G[7][4] = 1;
+    w->AT[3][7] = 1;
+    return true;
+  }
   return false;
 }
 
@@ -162,7 +196,7 @@ int winograd_layer_forward(int N, int C, int H, int W, int K, int m, int r, int 
       for (int ty = 0; ty < th; ++ty) {
         for (int tx = 0; tx < tw; ++tx) {
           const int64_t tau = ((int64_t)n * th + ty) * tw + tx;
-          real d[6][6], Btd[6][6];
+          real d[kMaxT][kMaxT], Btd[kMaxT][kMaxT];
           for (int i = 0; i < t; ++i) {
             for (int j = 0; j < t; ++j) {
               const int y = ty * m + i - pad, x = tx * m + j - pad;
@@ -212,7 +246,7 @@ int winograd_layer_forward(int N, int C, int H, int W, int K, int m, int r, int 
       for (int ty = 0; ty < th; ++ty) {
         for (int tx = 0; tx < tw; ++tx) {
           const int64_t tau = ((int64_t)n * th + ty) * tw + tx;
-          real z[6][6], Atz[4][6];
+          real z[kMaxT][kMaxT], Atz[4][kMaxT];
           for (int i = 0; i < t; ++i)
             for (int j = 0; j < t; ++j) z[i][j] = M[((int64_t)(i * t + j) * K + k) * T + tau];
           for (int a = 0; a < m; ++a) {
@@ -272,7 +306,7 @@ int winograd_layer_backward(int N, int C, int H, int W, int K, int m, int r, int
       for (int ty = 0; ty < th; ++ty) {
         for (int tx = 0; tx < tw; ++tx) {
           const int64_t tau = ((int64_t)n * th + ty) * tw + tx;
-          real d[6][6], Btd[6][6];
+          real d[kMaxT][kMaxT], Btd[kMaxT][kMaxT];
           for (int i = 0; i < t; ++i)
             for (int j = 0; j < t; ++j) {
               const int y = ty * m + i - pad, x = tx * m + j - pad;
@@ -303,7 +337,7 @@ int winograd_layer_backward(int N, int C, int H, int W, int K, int m, int r, int
       for (int ty = 0; ty < th; ++ty) {
         for (int tx = 0; tx < tw; ++tx) {
           const int64_t tau = ((int64_t)n * th + ty) * tw + tx;
-          real g[4][4], Ag[6][4];
+          real g[4][4], Ag[kMaxT][4];
           for (int a = 0; a < m; ++a)
             for (int b = 0; b < m; ++b) {
               const int y = ty * m + a, x = tx * m + b;
@@ -370,7 +404,7 @@ int winograd_layer_backward(int N, int C, int H, int W, int K, int m, int r, int
         for (int ty = 0; ty < th; ++ty) {
           for (int tx = 0; tx < tw; ++tx) {
             const int64_t tau = ((int64_t)n * th + ty) * tw + tx;
-            real f[6][6], Bf[6][6];
+            real f[kMaxT][kMaxT], Bf[kMaxT][kMaxT];
             for (int i = 0; i < t; ++i)
               for (int j = 0; j < t; ++j) f[i][j] = dV[((int64_t)(i * t + j) * C + c) * T + tau];
             for (int a = 0; a < t; ++a)
@@ -520,7 +554,7 @@ int oracle_wf_from_spatial_f64(int K, int C, int m, int r, const double* w, doub
   for (int k = 0; k < K; ++k)
     for (int c = 0; c < C; ++c) {
       const double* g = w + ((int64_t)k * C + c) * r * r;
-      double Gg[6][5];
+      double Gg[kMaxT][5];
       for (int i = 0; i < t; ++i)
         for (int v = 0; v < r; ++v) {
           double s = 0;

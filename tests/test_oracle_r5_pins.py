@@ -1,9 +1,9 @@
-"""Pins of the oracle for 5x5 kernels, F(2x2,5x5) (the paper times 3x3 and 5x5 layers, Section 6, and
-prints no matrices).  The layer is pinned to the definition it must reduce to: with W_F = G w G^T it equals
+"""Pins of the oracle for 5x5 kernels, F(2x2,5x5) and F(4x4,5x5) (the paper times 3x3 and 5x5 layers, Section 6,
+and prints no matrices).  The layer is pinned to the definition it must reduce to: with W_F = G w G^T it equals
 the direct 5x5 convolution (brute force and a library routine), which fails for any wrong entry of A, B or
 G; the position order by the single-non-zero closed form; the backward pass by the adjoint identities and
 the direct-convolution gradients.  The matrices themselves are pinned as the Vandermonde construction on the
-points {0, 1, -1, 2, -2, inf}."""
+points {0, 1, -1, 2, -2, inf} (F(4,5): with 1/2 and -1/2 added)."""
 from fractions import Fraction
 
 import numpy as np
@@ -13,7 +13,8 @@ import scipy.signal
 import oracle
 from paper_1702_08597_amd import synth
 
-M, R, T = 2, 5, 6
+R = 5
+MS = [2, 4]     # output tile sizes built for r = 5
 
 
 def dense_csr(P, K, C):
@@ -21,16 +22,31 @@ def dense_csr(P, K, C):
     return rowptr, np.tile(np.arange(C, dtype=np.int32), P * K)
 
 
-def test_matrices_match_the_hand_typed_fixture():
+@pytest.mark.parametrize("M", MS)
+def test_matrices_match_the_hand_typed_fixture(M):
     from test_oracle_pins import load_golden_matrices
-    gold = load_golden_matrices()[(2, 5)]
+    gold = load_golden_matrices()[(M, 5)]
     AT, BT, G = oracle.winograd_matrices(M, R)
     np.testing.assert_array_equal(AT, gold["AT"])
     np.testing.assert_array_equal(BT, gold["BT"])
     np.testing.assert_array_equal(G, gold["G"])
 
 
+@pytest.mark.parametrize("M", MS)
+def test_one_dimensional_minimal_filtering_identity(M):
+    # A^T[(G g) . (B^T d)] = the m outputs of the 5-tap correlation over m + 4 inputs, for unit vectors and random ones
+    AT, BT, G = oracle.winograd_matrices(M, R)
+    t = M + 4
+    rng = np.random.default_rng(M)
+    cases = [(np.eye(t)[a], np.eye(5)[b]) for a in range(t) for b in range(5)]
+    cases += [(rng.standard_normal(t), rng.standard_normal(5)) for _ in range(5)]
+    for d, g in cases:
+        want = [np.dot(d[a:a + 5], g) for a in range(M)]
+        np.testing.assert_allclose(AT @ ((G @ g) * (BT @ d)), want, rtol=0, atol=1e-12)
+
+
 def test_matrices_are_the_vandermonde_construction_on_the_f43_points():
+    M = 2
     AT, BT, G = oracle.winograd_matrices(M, R)
     assert AT.shape == (2, 6) and BT.shape == (6, 6) and G.shape == (6, 5)
     _, BT43, G43 = oracle.winograd_matrices(4, 3)
@@ -51,14 +67,15 @@ def test_matrices_are_the_vandermonde_construction_on_the_f43_points():
     np.testing.assert_allclose(AT @ ((G @ g) * (BT @ d)), want, rtol=0, atol=1e-13)
 
 
+@pytest.mark.parametrize("M", MS)
 @pytest.mark.parametrize("pad", [0, 2])
 @pytest.mark.parametrize("N,C,K,H,W", [(1, 1, 1, 5, 5), (2, 3, 2, 9, 7), (1, 2, 3, 27, 27), (1, 1, 2, 6, 13)])
-def test_layer_with_GwGT_equals_direct_5x5_convolution(pad, N, C, K, H, W):
+def test_layer_with_GwGT_equals_direct_5x5_convolution(M, pad, N, C, K, H, W):
     rng = np.random.default_rng(100 * pad + H + C)
     x = rng.standard_normal((N, C, H, W))
     w = rng.standard_normal((K, C, 5, 5))
     wf = oracle.wf_from_spatial_f64(w, M)
-    rp, ci = dense_csr(36, K, C)
+    rp, ci = dense_csr((M + 4) ** 2, K, C)
     out = oracle.forward_f64(x, rp, ci, wf.reshape(-1), K, M, R, pad, want_VM=False)[0]
     brute = oracle.direct_conv_f64(x, w, pad)
     xp = np.pad(x, ((0, 0), (0, 0), (pad, pad), (pad, pad)))
@@ -69,19 +86,21 @@ def test_layer_with_GwGT_equals_direct_5x5_convolution(pad, N, C, K, H, W):
                 lib[n, k] += scipy.signal.correlate2d(xp[n, c], w[k, c], mode="valid")
     scale = max(1.0, np.abs(lib).max())
     assert np.abs(brute - lib).max() <= 1e-12 * scale
-    assert np.abs(out - lib).max() <= 1e-11 * scale
+    assert np.abs(out - lib).max() <= (1e-11 if M == 2 else 1e-10) * scale
 
 
-def test_single_nonzero_closed_form_fixes_the_position_order():
+@pytest.mark.parametrize("M", MS)
+def test_single_nonzero_closed_form_fixes_the_position_order(M):
+    T = M + 4
     N, C, K, H, W, pad = 1, 2, 2, 8, 6, 2
     rng = np.random.default_rng(7)
     x = rng.standard_normal((N, C, H, W))
     AT, BT, _ = oracle.winograd_matrices(M, R)
     i, j, k, c, wv = 1, 4, 1, 0, 0.75
-    rowptr = np.zeros(36 * K + 1, dtype=np.int32)
+    rowptr = np.zeros(T * T * K + 1, dtype=np.int32)
     rowptr[(i * T + j) * K + k + 1:] = 1
     out = oracle.forward_f64(x, rowptr, np.array([c], np.int32), np.array([wv]), K, M, R, pad, want_VM=False)[0]
-    xp = np.pad(x, ((0, 0), (0, 0), (pad, pad + 2), (pad, pad + 2)))
+    xp = np.pad(x, ((0, 0), (0, 0), (pad, pad + M), (pad, pad + M)))
     th, tw = -(-out.shape[2] // M), -(-out.shape[3] // M)
     for ty in range(th):
         for tx in range(tw):
@@ -92,14 +111,16 @@ def test_single_nonzero_closed_form_fixes_the_position_order():
     assert np.all(out[0, 0] == 0)
 
 
+@pytest.mark.parametrize("M", MS)
 @pytest.mark.parametrize("pad,H,W", [(2, 9, 9), (0, 8, 11), (1, 6, 7)])
-def test_backward_adjoint_identities_and_direct_convolution_gradients(pad, H, W):
+def test_backward_adjoint_identities_and_direct_convolution_gradients(M, pad, H, W):
+    P = (M + 4) ** 2
     rng = np.random.default_rng(300 + pad)
     N, C, K = 2, 3, 4
     x = rng.standard_normal((N, C, H, W))
     Ho, Wo = H + 2 * pad - 4, W + 2 * pad - 4
     G = rng.standard_normal((N, K, Ho, Wo))
-    rp, ci, va = synth.bernoulli_weights(36, K, C, 0.6, 301)
+    rp, ci, va = synth.bernoulli_weights(P, K, C, 0.6, 301)
     va = rng.standard_normal(va.shape)
     out, V, Mm = oracle.forward_f64(x, rp, ci, va, K, M, R, pad)
     din, dvals, dZ, dV = oracle.backward_f64(x, rp, ci, va, G, K, M, R, pad)
@@ -110,11 +131,11 @@ def test_backward_adjoint_identities_and_direct_convolution_gradients(pad, H, W)
     # dense W_F = G w G^T: the input gradient is the direct convolution's
     w = rng.standard_normal((K, C, 5, 5))
     wf = oracle.wf_from_spatial_f64(w, M)
-    rpd, cid = dense_csr(36, K, C)
+    rpd, cid = dense_csr(P, K, C)
     din2 = oracle.backward_f64(x, rpd, cid, wf.reshape(-1), G, K, M, R, pad, want_ZV=False)[0]
     dxp = np.zeros((N, C, H + 2 * pad, W + 2 * pad))
     for u in range(5):
         for v in range(5):
             dxp[:, :, u:u + Ho, v:v + Wo] += np.einsum("nkyx,kc->ncyx", G, w[:, :, u, v])
     ref = dxp[:, :, pad:pad + H, pad:pad + W]
-    np.testing.assert_allclose(din2, ref, rtol=0, atol=1e-11 * np.abs(ref).max())
+    np.testing.assert_allclose(din2, ref, rtol=0, atol=(1e-11 if M == 2 else 1e-10) * np.abs(ref).max())
