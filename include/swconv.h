@@ -19,8 +19,9 @@
  *   - fp32 data, int32 indices.  Unit stride and dilation, square r x r kernel, square m x m
  *     output tile (Section 3 assumes unit stride/dilation; A1=A2, B1=B2 when r=s, m=n).
  *   - Supported F(m x m, r x r): (m,r) = (2,3), (4,3) and, for the 5x5 layers of Section 6
- *     (Table 1), (2,5).  A, B are the standard minimal-filtering matrices for points {0,1,-1,inf}
- *     and {0,1,-1,2,-2,inf} (the paper defers to Lavin & Gray for their values):
+ *     (Table 1), (2,5) and (4,5).  A, B are the standard minimal-filtering matrices for points
+ *     {0,1,-1,inf}, {0,1,-1,2,-2,inf} and {0,1,-1,2,-2,1/2,-1/2,inf} (the paper defers to Lavin &
+ *     Gray for the 3x3 values and names no 5x5 ones):
  *       F(2,3): B^T = [1 0 -1 0; 0 1 1 0; 0 -1 1 0; 0 1 0 -1],  A^T = [1 1 1 0; 0 1 -1 -1]
  *       F(4,3): B^T = [4 0 -5 0 1 0; 0 -4 -4 1 1 0; 0 4 -4 -1 1 0; 0 -2 -1 2 1 0;
  *                      0 2 -1 -2 1 0; 0 4 0 -5 0 1]
@@ -30,6 +31,15 @@
  *                [1/4 0 0 0 0], -1/6 [1 1 1 1 1], -1/6 [1 -1 1 -1 1], 1/24 [1 2 4 8 16],
  *                1/24 [1 -2 4 -8 16], [0 0 0 0 1]; the library itself never applies it: W_F is
  *                given in the Winograd domain)
+ *       F(4,5): t = 8.  Row i of B^T = coefficients, ascending powers, of prod_{k != i} (x - p_k)
+ *               over the seven finite points p = (0, 1, -1, 2, -2, 1/2, -1/2), last row those of
+ *               prod_k (x - p_k):
+ *               B^T = [-1 0 21/4 0 -21/4 0 1 0; 0 1 1 -17/4 -17/4 1 1 0; 0 -1 1 17/4 -17/4 -1 1 0;
+ *                      0 1/2 1/4 -5/2 -5/4 2 1 0; 0 -1/2 1/4 5/2 -5/4 -2 1 0; 0 2 4 -5/2 -5 1/2 1 0;
+ *                      0 -2 4 5/2 -5 -1/2 1 0; 0 -1 0 21/4 0 -21/4 0 1]
+ *               A^T = [1 1 1 1 1 1 1 0; 0 1 -1 2 -2 1/2 -1/2 0; 0 1 1 4 4 1/4 1/4 0;
+ *                      0 1 -1 8 -8 1/8 -1/8 1]
+ *               (matching filter transform: G[i][j] = p_i^j / prod_{k != i} (p_i - p_k), last row e_4)
  *   - Ho = H + 2*pad - r + 1, Wo likewise; th = ceil(Ho/m), tw = ceil(Wo/m); T = N*th*tw.
  *     Tile tau = (n*th + ty)*tw + tx reads input rows ty*m - pad ... ty*m - pad + t - 1 (zero
  *     outside the image: this covers both the convolution padding and a ragged last tile, per

@@ -34,7 +34,8 @@
 // Readings where the paper is silent (kept identical in the GPU library's
 // documentation):
 //   * A, B, G are the standard minimal-filtering matrices for interpolation
-//     points {0, 1, -1, inf} (F(2,3)) and {0, 1, -1, 2, -2, inf} (F(4,3), F(2,5));
+//     points {0, 1, -1, inf} (F(2,3)), {0, 1, -1, 2, -2, inf} (F(4,3), F(2,5)) and, with 1/2 and -1/2
+//     added, F(4,5);
 //     Section 3 only says the F(2x2,3x3) ones have entries 0, +-1, +-1/2.
 //   * position index p = i*t + j, i = row of the transformed tile.
 //   * tile index tau = (n*th + ty)*tw + tx, th = ceil(H_o/m), tw = ceil(W_o/m);

@@ -215,7 +215,9 @@ int launch_kernel(void (*kern)(Params...), dim3 grid, dim3 block, size_t lds, co
 template <typename F>
 int dispatch_mr(const swconv_plan* pl, F&& f) {
   using std::integral_constant;
-  if (pl->r == 5) return f(integral_constant<int, 2>{}, integral_constant<int, 5>{});
+  if (pl->r == 5)
+    return pl->m == 2 ? f(integral_constant<int, 2>{}, integral_constant<int, 5>{})
+                      : f(integral_constant<int, 4>{}, integral_constant<int, 5>{});
   return pl->m == 2 ? f(integral_constant<int, 2>{}, integral_constant<int, 3>{})
                     : f(integral_constant<int, 4>{}, integral_constant<int, 3>{});
 }
@@ -950,7 +952,7 @@ const char* swconv_status_string(int status) {
 int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int m, int r, int pad) {
   if (!out) return SWCONV_EINVAL;
   if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || pad < 0 || m < 1 || r < 1) return SWCONV_EINVAL;
-  if (!((m == 2 && r == 3) || (m == 4 && r == 3) || (m == 2 && r == 5))) return SWCONV_EUNSUPPORTED;
+  if (!((m == 2 || m == 4) && (r == 3 || r == 5))) return SWCONV_EUNSUPPORTED;
   const int64_t Ho = (int64_t)H + 2 * pad - r + 1, Wo = (int64_t)W + 2 * pad - r + 1;
   if (Ho < 1 || Wo < 1) return SWCONV_EINVAL;
   const int t = m + r - 1, P = t * t;
@@ -1014,8 +1016,9 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   {
     const int G = (int)std::min<int64_t>(N, std::max<int64_t>(1, 64 / g.tpi));
     const int64_t wave_floats = ((int64_t)G * H * W + 63) / 64 * 64 + 64;
-    // (with patches reaching two tiles back, F(2x2,5x5), its nine phases measured slower than the two kernels)
-    if (4 * wave_floats * (int64_t)sizeof(float) <= kMaxLdsBytes && (t - 1) / m == 1 &&
+    // (with patches reaching two tiles back, F(2x2,5x5), its nine phases measured slower than the two kernels;
+    // with 8 x 8 patches, F(4x4,5x5), patch, transform and LDS indices together overflow the 256 vector registers)
+    if (4 * wave_floats * (int64_t)sizeof(float) <= kMaxLdsBytes && (t - 1) / m == 1 && t <= 6 &&
         env_int("SWCONV_FUSE_INPUT_GRAD", 1) != 0) {
       try {
         GradTile none;

@@ -220,7 +220,10 @@ __global__ __launch_bounds__(256) void input_transform_kernel(const float* __res
     // the selects below into one guarded (and serialised) read each
 #pragma unroll
     for (int i = 0; i < t; ++i) {
-      if constexpr (t == 6)
+      if constexpr (t == 8)
+        asm volatile("" : "+v"(d[i][0]), "+v"(d[i][1]), "+v"(d[i][2]), "+v"(d[i][3]), "+v"(d[i][4]), "+v"(d[i][5]),
+                          "+v"(d[i][6]), "+v"(d[i][7]));
+      else if constexpr (t == 6)
         asm volatile("" : "+v"(d[i][0]), "+v"(d[i][1]), "+v"(d[i][2]), "+v"(d[i][3]), "+v"(d[i][4]), "+v"(d[i][5]));
       else
         asm volatile("" : "+v"(d[i][0]), "+v"(d[i][1]), "+v"(d[i][2]), "+v"(d[i][3]));

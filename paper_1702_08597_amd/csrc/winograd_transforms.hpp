@@ -7,6 +7,9 @@
 // {0,1,-1,inf} and {0,1,-1,2,-2,inf}.  F(2,5) (the 5x5 layers of Section 6) has t = 6 like F(4,3) and
 // is built on the same six points, so it shares B^T with F(4,3); its A^T keeps the first two rows of
 // the F(4,3) one, with the point at infinity entering the row of the highest output power.
+// F(4,5), t = 8, is the same Toom-Cook construction on {0,1,-1,2,-2,1/2,-1/2,inf}: row i of B^T holds
+// the coefficients of prod_{k != i} (x - p_k) (last row: of prod_k (x - p_k)), A^T[a][i] = p_i^a; all
+// entries are dyadic rationals.
 //
 // The 1-D transforms are written out by hand (shared sub-expressions, no multiplications by
 // 0 or +-1); the 2-D sandwich applies them to columns, then to rows.
@@ -17,7 +20,8 @@ namespace swconv {
 
 template <int M, int R>
 struct Wino {
-  static_assert((M == 2 && R == 3) || (M == 4 && R == 3) || (M == 2 && R == 5), "F(m x m, r x r) not built");
+  static_assert((M == 2 && R == 3) || (M == 4 && R == 3) || (M == 2 && R == 5) || (M == 4 && R == 5),
+                "F(m x m, r x r) not built");
   static constexpr int m = M, r = R, t = M + R - 1;
 };
 
@@ -50,6 +54,25 @@ __device__ __forceinline__ void bt_apply<6>(const float (&x)[6], float (&r)[6]) 
   r[5] = fmaf(4.0f, x[1], fmaf(-5.0f, x[3], x[5]));
 }
 
+//   t = 8:  B^T = [-1 0 21/4 0 -21/4 0 1 0; 0 1 1 -17/4 -17/4 1 1 0; 0 -1 1 17/4 -17/4 -1 1 0;
+//                  0 1/2 1/4 -5/2 -5/4 2 1 0; 0 -1/2 1/4 5/2 -5/4 -2 1 0; 0 2 4 -5/2 -5 1/2 1 0;
+//                  0 -2 4 5/2 -5 -1/2 1 0; 0 -1 0 21/4 0 -21/4 0 1]
+// rows 1..6 come in pairs that share their even-index part and differ in the sign of the odd one
+template <>
+__device__ __forceinline__ void bt_apply<8>(const float (&x)[8], float (&r)[8]) {
+  const float e12 = fmaf(-4.25f, x[4], x[2]) + x[6], o12 = fmaf(-4.25f, x[3], x[1]) + x[5];
+  const float e34 = fmaf(0.25f, x[2], fmaf(-1.25f, x[4], x[6])), o34 = fmaf(0.5f, x[1], fmaf(-2.5f, x[3], 2.0f * x[5]));
+  const float e56 = fmaf(4.0f, x[2], fmaf(-5.0f, x[4], x[6])), o56 = fmaf(2.0f, x[1], fmaf(-2.5f, x[3], 0.5f * x[5]));
+  r[0] = fmaf(5.25f, x[2] - x[4], x[6] - x[0]);
+  r[1] = e12 + o12;
+  r[2] = e12 - o12;
+  r[3] = e34 + o34;
+  r[4] = e34 - o34;
+  r[5] = e56 + o56;
+  r[6] = e56 - o56;
+  r[7] = fmaf(5.25f, x[3] - x[5], x[7] - x[1]);
+}
+
 // y = A^T z for one column (or row).
 //   F(2,3): A^T = [1 1 1 0; 0 1 -1 -1]
 //   F(4,3): A^T = [1 1 1 1 1 0; 0 1 -1 2 -2 0; 0 1 1 4 4 0; 0 1 -1 8 -8 1]
@@ -79,6 +102,18 @@ __device__ __forceinline__ void at_apply<2, 5>(const float (&z)[6], float (&y)[2
   const float s34 = z[3] + z[4], d34 = z[3] - z[4];
   y[0] = z[0] + s12 + s34;
   y[1] = fmaf(2.0f, d34, d12) + z[5];
+}
+
+//   F(4,5): A^T = [1 1 1 1 1 1 1 0; 0 1 -1 2 -2 1/2 -1/2 0; 0 1 1 4 4 1/4 1/4 0; 0 1 -1 8 -8 1/8 -1/8 1]
+template <>
+__device__ __forceinline__ void at_apply<4, 5>(const float (&z)[8], float (&y)[4]) {
+  const float s12 = z[1] + z[2], d12 = z[1] - z[2];
+  const float s34 = z[3] + z[4], d34 = z[3] - z[4];
+  const float s56 = z[5] + z[6], d56 = z[5] - z[6];
+  y[0] = z[0] + s12 + s34 + s56;
+  y[1] = fmaf(2.0f, d34, fmaf(0.5f, d56, d12));
+  y[2] = fmaf(4.0f, s34, fmaf(0.25f, s56, s12));
+  y[3] = fmaf(8.0f, d34, fmaf(0.125f, d56, d12)) + z[7];
 }
 
 // v = B^T d B  (t x t): columns first, then rows.
@@ -144,6 +179,21 @@ __device__ __forceinline__ void a_apply<2, 5>(const float (&g)[2], float (&z)[6]
 }
 
 template <>
+__device__ __forceinline__ void a_apply<4, 5>(const float (&g)[4], float (&z)[8]) {
+  const float e1 = g[0] + g[2], o1 = g[1] + g[3];
+  const float e2 = fmaf(4.0f, g[2], g[0]), o2 = fmaf(8.0f, g[3], 2.0f * g[1]);
+  const float e5 = fmaf(0.25f, g[2], g[0]), o5 = fmaf(0.125f, g[3], 0.5f * g[1]);
+  z[0] = g[0];
+  z[1] = e1 + o1;
+  z[2] = e1 - o1;
+  z[3] = e2 + o2;
+  z[4] = e2 - o2;
+  z[5] = e5 + o5;
+  z[6] = e5 - o5;
+  z[7] = g[3];
+}
+
+template <>
 __device__ __forceinline__ void a_apply<4, 3>(const float (&g)[4], float (&z)[6]) {
   const float e = g[0] + g[2], o = g[1] + g[3];                            // even / odd sums
   const float e4 = fmaf(4.0f, g[2], g[0]), o4 = fmaf(8.0f, g[3], 2.0f * g[1]);  // g0 + 4 g2, 2 g1 + 8 g3
@@ -177,6 +227,21 @@ __device__ __forceinline__ void b_apply<6>(const float (&f)[6], float (&d)[6]) {
   d[3] = fmaf(2.0f, d34, fmaf(-5.0f, f[5], d12));
   d[4] = f[0] + s12 + s34;
   d[5] = f[5];
+}
+
+template <>
+__device__ __forceinline__ void b_apply<8>(const float (&f)[8], float (&d)[8]) {
+  const float s12 = f[1] + f[2], d12 = f[1] - f[2];
+  const float s34 = f[3] + f[4], d34 = f[3] - f[4];
+  const float s56 = f[5] + f[6], d56 = f[5] - f[6];
+  d[0] = -f[0];
+  d[1] = fmaf(0.5f, d34, fmaf(2.0f, d56, d12)) - f[7];
+  d[2] = fmaf(5.25f, f[0], fmaf(0.25f, s34, fmaf(4.0f, s56, s12)));
+  d[3] = fmaf(-4.25f, d12, fmaf(-2.5f, d34 + d56, 5.25f * f[7]));
+  d[4] = fmaf(-5.25f, f[0], fmaf(-4.25f, s12, fmaf(-1.25f, s34, -5.0f * s56)));
+  d[5] = fmaf(2.0f, d34, fmaf(0.5f, d56, fmaf(-5.25f, f[7], d12)));
+  d[6] = f[0] + s12 + s34 + s56;
+  d[7] = f[7];
 }
 
 // z = A g A^T  (t x t from m x m): columns first, then rows.

@@ -26,6 +26,7 @@ CONFIGS = {
     "vgg_56_n32_f4": dict(N=32, C=256, H=56, W=56, K=256, m=4, r=3, pad=1, density=0.10, seed=BASE_SEED + 5),
     # one of the two channel groups of AlexNet's 5x5 layer (Table 1: conv2, 90.6 % sparse under method A)
     "alexnet_conv2g_n32_f2r5": dict(N=32, C=48, H=27, W=27, K=128, m=2, r=5, pad=2, density=0.094, seed=BASE_SEED + 7),
+    "alexnet_conv2g_n32_f4r5": dict(N=32, C=48, H=27, W=27, K=128, m=4, r=5, pad=2, density=0.094, seed=BASE_SEED + 8),
     "conv4_skewed_n64_f4": dict(N=64, C=384, H=13, W=13, K=384, m=4, r=3, pad=1, density=None, seed=BASE_SEED + 6),
 }
 BENCH_CONFIG = "alexnet_conv3_n32_f4"

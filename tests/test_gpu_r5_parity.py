@@ -1,8 +1,12 @@
-"""GPU parity of the 5x5 layer, F(2x2,5x5) (t = 6, P = 36), forward and backward, through the C ABI.
+"""GPU parity of the 5x5 layer, F(2x2,5x5) (t = 6, P = 36) and F(4x4,5x5) (t = 8, P = 64), forward and
+backward, through the C ABI.
 
 Tolerance: F(2,5) uses the input transform of F(4,3) (same interpolation points, same B^T with
 entries up to 5), so the bound of F(4x4,3x3) applies: max|gpu - oracle64| <= 1e-4 * max|oracle64|
-over a whole tensor.  Integer-valued data must match bit for bit.
+over a whole tensor; F(4,5) adds the points +-1/2 (entries up to 21/4 and 8) and the oracle's own
+float instantiation stays below 1e-6 of the fp64 one on these inputs, so the same bound is kept.
+Integer-valued data must match bit for bit for F(2,5); F(4,5) has entries down to 1/8, whose
+products with integers need more than 24 bits at these magnitudes, so it is checked by tolerance.
 """
 import numpy as np
 import pytest
@@ -208,8 +212,78 @@ def test_rows_longer_than_the_fused_kernels_batches_fall_back():
         sw.swconv_plan_destroy(plan)
 
 
+F45 = [
+    # N, C, H, W, K, pad
+    (3, 7, 13, 11, 9, 2),
+    (2, 5, 27, 27, 6, 2),
+    (9, 4, 8, 9, 5, 0),
+    (1, 1, 5, 5, 1, 0),      # one output pixel
+    (1, 2, 1, 1, 3, 2),      # one input pixel
+    (70, 3, 4, 4, 4, 2),     # one tile per image, many images
+    (2, 6, 9, 12, 300, 1),
+]
+
+
+@pytest.mark.parametrize("N,C,H,W,K,pad", F45)
+def test_f4x4_5x5_all_stages(N, C, H, W, K, pad):
+    print("F(4,5) case N=%d C=%d H=%d W=%d K=%d pad=%d" % (N, C, H, W, K, pad), flush=True)
+    x = synth.activations(N, C, H, W, 1500 + N + C)
+    rp, ci, va = synth.bernoulli_weights(64, K, C, 0.3, 1600 + K)
+    Ho, Wo = H + 2 * pad - 4, W + 2 * pad - 4
+    G = np.random.default_rng(1700 + N).standard_normal((N, K, Ho, Wo)).astype(np.float32)
+    o64, V64, M64 = oracle.forward_f64(x, rp, ci, va, K, 4, 5, pad)
+    din64, dvals64, dZ64, dV64 = oracle.backward_f64(x, rp, ci, va, G, K, 4, 5, pad)
+    ref = dict(out=o64, V=V64, M=M64, din=din64, dvals=dvals64, dZ=dZ64, dV=dV64)
+    plan = sw.swconv_plan_create(N, C, H, W, K, 4, 5, pad)
+    try:
+        assert sw.swconv_plan_sizes(plan)[0] == 64
+        sw.swconv_set_weights(plan, rp, ci, va)
+        xd, gd = torch.from_numpy(x).cuda(), torch.from_numpy(G).cuda()
+        out = torch.full((N, K, Ho, Wo), float("nan"), device="cuda")
+        din = torch.full((N, C, H, W), float("nan"), device="cuda")
+        dv = torch.full((max(1, len(va)),), float("nan"), device="cuda")
+        sw.swconv_forward(plan, 0, xd.data_ptr(), out.data_ptr())
+        torch.cuda.synchronize()
+        got = dict(out=out.cpu().numpy(), V=sw.swconv_debug_copy_V(plan, C), M=sw.swconv_debug_copy_M(plan, K))
+        sw.swconv_backward(plan, 0, xd.data_ptr(), gd.data_ptr(), din.data_ptr(), dv.data_ptr())
+        torch.cuda.synchronize()
+        got.update(din=din.cpu().numpy(), dvals=dv.cpu().numpy()[:len(va)], dZ=sw.swconv_debug_copy_dZ(plan, K),
+                   dV=sw.swconv_debug_copy_dV(plan, C))
+    finally:
+        sw.swconv_plan_destroy(plan)
+    for name in ("V", "M", "out", "dZ", "dV", "din", "dvals"):
+        assert not np.isnan(got[name]).any(), name + " not fully overwritten"
+        e = relerr(got[name], ref[name])
+        print("  %-5s max rel err %.3g" % (name, e), flush=True)
+        assert e <= RTOL, name
+
+
+def test_alexnet_conv2_group_full_size_f4x4():
+    cfg, x, rp, ci, va = synth.make_layer("alexnet_conv2g_n32_f4r5")
+    N, C, H, W, K, pad = (cfg[k] for k in ("N", "C", "H", "W", "K", "pad"))
+    G = np.random.default_rng(cfg["seed"] + 5).standard_normal((N, K, cfg["Ho"], cfg["Wo"])).astype(np.float32)
+    o64, _, _ = oracle.forward_f64(x, rp, ci, va, K, 4, 5, pad, want_VM=False)
+    din64, dvals64, _, _ = oracle.backward_f64(x, rp, ci, va, G, K, 4, 5, pad, want_ZV=False)
+    plan = sw.swconv_plan_create(N, C, H, W, K, 4, 5, pad)
+    try:
+        sw.swconv_set_weights(plan, rp, ci, va)
+        xd, gd = torch.from_numpy(x).cuda(), torch.from_numpy(G).cuda()
+        out = torch.full(o64.shape, float("nan"), dtype=torch.float32, device="cuda")
+        din = torch.full(x.shape, float("nan"), dtype=torch.float32, device="cuda")
+        dv = torch.full((len(va),), float("nan"), device="cuda")
+        sw.swconv_forward(plan, 0, xd.data_ptr(), out.data_ptr())
+        sw.swconv_backward(plan, 0, 0, gd.data_ptr(), din.data_ptr(), dv.data_ptr())
+        torch.cuda.synchronize()
+        for name, got, ref in (("out", out, o64), ("din", din, din64), ("dvals", dv, dvals64)):
+            e = relerr(got.cpu().numpy(), ref)
+            print("  %-5s max rel err %.3g" % (name, e), flush=True)
+            assert e <= RTOL, name
+    finally:
+        sw.swconv_plan_destroy(plan)
+
+
 def test_other_filter_sizes_are_refused():
-    for m, r in ((4, 5), (2, 7), (3, 3), (6, 3)):
+    for m, r in ((3, 5), (2, 7), (3, 3), (6, 3)):
         with pytest.raises(sw.SwconvError) as e:
             sw.swconv_plan_create(1, 4, 16, 16, 4, m, r, 1)
         assert e.value.status == sw.SWCONV_EUNSUPPORTED

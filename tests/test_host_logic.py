@@ -35,7 +35,7 @@ def test_status_strings():
     ((1, 4, 8, 8, 4, 4, 3, -1), sw.SWCONV_EINVAL),
     ((1, 4, 2, 8, 4, 4, 3, 0), sw.SWCONV_EINVAL),      # Ho < 1
     ((1, 4, 8, 8, 4, 3, 3, 1), sw.SWCONV_EUNSUPPORTED),  # F(3,3)
-    ((1, 4, 8, 8, 4, 4, 5, 1), sw.SWCONV_EUNSUPPORTED),  # F(4,5): only F(2,5) is built for r = 5
+    ((1, 4, 8, 8, 4, 6, 5, 1), sw.SWCONV_EUNSUPPORTED),  # F(6,5): m = 2 and 4 are built for r = 5
     ((1, 4096, 8, 8, 4, 4, 3, 1), sw.SWCONV_EUNSUPPORTED),  # panel beyond LDS
 ])
 def test_plan_create_rejects(args, status):
@@ -176,7 +176,7 @@ def test_schedule_is_a_partition_for_random_shapes_and_cost_settings(seed, env, 
         monkeypatch.setenv(k, v)
     rng = np.random.default_rng(9000 + seed)
     for _ in range(4):
-        m, r = [(2, 3), (4, 3), (2, 5)][int(rng.integers(0, 3))]
+        m, r = [(2, 3), (4, 3), (2, 5), (4, 5)][int(rng.integers(0, 4))]
         N, C, K = int(rng.integers(1, 70)), int(rng.integers(1, 400)), int(rng.integers(1, 500))
         H, W = int(rng.integers(r, 30)), int(rng.integers(r, 30))
         P = (m + r - 1) ** 2
