@@ -187,6 +187,17 @@ int swconv_set_weights_device(swconv_plan* plan, void* hip_stream, const int32_t
                               const int32_t* colidx_dev, const float* vals_dev);
 
 /*
+ * Fine-tuning with the sparsity pattern fixed (Section 4.3): new values for the weights set last,
+ * same rowptr and colidx.  Nothing is re-packed and nothing crosses to the host: one small kernel
+ * per packed copy of W_F (the forward stream, the fused kernel's packages, the transposed stream of
+ * the backward pass if it exists) writes the values in place, enqueued on `hip_stream`.
+ *   vals_dev  DEVICE, nnz floats in the order of the colidx passed to swconv_set_weights.
+ * Passes enqueued later on the same stream see the new values; a pass on another stream needs
+ * the caller's own ordering.  Errors: ESTATE (no weights), EINVAL (null), EHIP.
+ */
+int swconv_update_values(swconv_plan* plan, void* hip_stream, const float* vals_dev);
+
+/*
  * Measurement helper for the backward pass: `iters` passes with every kernel launched with its own
  * pair of HIP events (as swconv_profile_forward); mean milliseconds per kernel, in launch order:
  *   stage_ms  HOST, 7 floats: dL/dZ transform, input transform (I_F again), sampled products,

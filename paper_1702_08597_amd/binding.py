@@ -19,6 +19,7 @@ EXPORTS = [
     "swconv_plan_weight_stats", "swconv_debug_check_schedule",
     "swconv_backward", "swconv_debug_copy_dZ", "swconv_debug_copy_dV", "swconv_profile_backward",
     "swconv_prune_step", "swconv_set_weights_device", "swconv_plan_set_image_strides",
+    "swconv_update_values",
 ]
 
 _lib = None
@@ -59,6 +60,7 @@ def lib():
                                                ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int64)]
         L.swconv_debug_check_schedule.argtypes = [_vp]
         L.swconv_plan_set_image_strides.argtypes = [_vp, ctypes.c_int64, ctypes.c_int64]
+        L.swconv_update_values.argtypes = [_vp, _vp, _vp]
         L.swconv_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
         L.swconv_profile_backward.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int, _f32p]
         L.swconv_prune_step.argtypes = [ctypes.c_int64, _vp, _vp, _vp, _vp] + [ctypes.c_float] * 4 + [_vp] * 5
@@ -177,6 +179,10 @@ def swconv_profile_forward(plan, stream, in_dev_ptr, out_dev_ptr, iters):
     _check(lib().swconv_profile_forward(plan, _vp(stream), _vp(in_dev_ptr), _vp(out_dev_ptr), int(iters),
                                         ms.ctypes.data_as(_f32p)), "swconv_profile_forward")
     return ms
+
+
+def swconv_update_values(plan, stream, vals_dev_ptr):
+    _check(lib().swconv_update_values(plan, _vp(stream), _vp(vals_dev_ptr)), "swconv_update_values")
 
 
 def swconv_plan_set_image_strides(plan, in_stride, out_stride):

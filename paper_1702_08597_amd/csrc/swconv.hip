@@ -130,12 +130,14 @@ struct FusedProduct {
   int KC = 0;             // row chunks of kFusedRows
   int B = 0;              // batches per slice and position (the longest row decides)
   std::vector<uint32_t> wpk;
+  std::vector<int32_t> value_index;  // per pair of wpk: index into the caller's value array, -1 = padding
   std::vector<uint8_t> lens;
   std::vector<OutTile> otiles;
   uint32_t* d_wpk = nullptr;
   uint8_t* d_lens = nullptr;
   OutTile* d_otiles = nullptr;
-  size_t cap_wpk = 0, cap_lens = 0;
+  int32_t* d_value_index = nullptr;
+  size_t cap_wpk = 0, cap_lens = 0, cap_value_index = 0;
 };
 
 struct swconv_plan {
@@ -169,6 +171,11 @@ struct swconv_plan {
   int32_t* d_entry_index = nullptr;
   size_t cap_entry_index = 0;
   bool index_current = false;
+  // swconv_update_values: the device streams hold newer values than the host copies
+  bool host_values_stale = false;
+  std::vector<int32_t> bt_value_index;  // per pair of the packed W_F^T: index into the caller's value array
+  int32_t* d_bt_value_index = nullptr;
+  size_t cap_bt_value_index = 0;
   bool ran_backward = false;
   float* d_wdense = nullptr;  // [P][C][Kq]
 };
@@ -403,6 +410,7 @@ void pack_fused(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, c
   const size_t dwords = (size_t)P * fz.KC * fz.B * kFusedWaves * 128;
   if (dwords * 4 >= ((size_t)1 << 32) - 4096) return;
   fz.wpk.assign(dwords, 0u);
+  fz.value_index.assign(dwords / 2, -1);
   fz.lens.assign((size_t)P * spp, 0);
   const uint32_t row_bytes = (uint32_t)kTileBlock * sizeof(float);
   for (int p = 0; p < P; ++p)
@@ -416,6 +424,7 @@ void pack_fused(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, c
         uint32_t* entry = &fz.wpk[batch * 128 + ((size_t)q * kBatchSteps + e % kBatchSteps) * 2];
         entry[0] = (uint32_t)colidx[q0 + e] * row_bytes;
         std::memcpy(&entry[1], &vals[q0 + e], sizeof(float));
+        fz.value_index[(size_t)(entry - fz.wpk.data()) / 2] = q0 + e;
       }
     }
   fz.ready = true;
@@ -428,6 +437,7 @@ int upload_fused(swconv_plan* pl) {
   int rc;
   if ((rc = upload(&fz.d_wpk, fz.wpk, &fz.cap_wpk))) return rc;
   if ((rc = upload(&fz.d_lens, fz.lens, &fz.cap_lens))) return rc;
+  if ((rc = upload(&fz.d_value_index, fz.value_index, &fz.cap_value_index))) return rc;
   if (!fz.d_otiles && (rc = upload(&fz.d_otiles, fz.otiles))) return rc;
   HIP_TRY(hipDeviceSynchronize());
   fz.ready = true;
@@ -785,6 +795,16 @@ int copy_padded_to_host(const float* dsrc, float* hdst, size_t rows, int T, int 
   return SWCONV_OK;
 }
 
+// After swconv_update_values the device stream of W_F holds the current values: fetch it before
+// the host copy is read (transposition for the backward pass, export).
+int refresh_host_values(swconv_plan* pl) {
+  if (!pl->host_values_stale) return SWCONV_OK;
+  HIP_TRY(hipDeviceSynchronize());
+  HIP_TRY(hipMemcpy(pl->fw.stream.data(), pl->fw.d_stream, pl->fw.stream.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
+  pl->host_values_stale = false;
+  return SWCONV_OK;
+}
+
 // Packs W_F^T (per position: C rows of (k, weight) entries, k ascending) from the packed W_F and
 // allocates the dL/dI_F workspace.  Host work; done by the first backward pass after set_weights.
 int prepare_backward(swconv_plan* pl) {
@@ -795,6 +815,9 @@ int prepare_backward(swconv_plan* pl) {
     const int64_t nnz = pl->fw.nnz;
     std::vector<int32_t> rp((size_t)P * K + 1), ci((size_t)nnz), trp((size_t)P * C + 1, 0), tci((size_t)nnz);
     std::vector<float> va((size_t)nnz), tva((size_t)nnz);
+    std::vector<int32_t> t_to_orig((size_t)nnz);  // entry of the transposed CSR -> entry of the caller's CSR
+    int rc0 = refresh_host_values(pl);
+    if (rc0) return rc0;
     unpack_matrix(pl->fw, P, rp.data(), ci.data(), va.data());
     for (int p = 0; p < P; ++p)
       for (int32_t q = rp[(size_t)p * K]; q < rp[(size_t)(p + 1) * K]; ++q) ++trp[(size_t)p * C + ci[q] + 1];
@@ -806,15 +829,20 @@ int prepare_backward(swconv_plan* pl) {
           const int32_t dst = fill[(size_t)p * C + ci[q]]++;
           tci[dst] = k;
           tva[dst] = va[q];
+          t_to_orig[dst] = q;
         }
     size_grid(&pl->bt, (int64_t)P * pl->n_tau_blocks * (pl->bt.rows_padded / kSliceRows));
     pack_matrix(&pl->bt, P, pl->n_tau_blocks, trp.data(), tci.data(), tva.data());
+    pl->bt_value_index.assign(pl->bt.entry_index.size(), -1);
+    for (size_t e = 0; e < pl->bt.entry_index.size(); ++e)
+      if (pl->bt.entry_index[e] >= 0) pl->bt_value_index[e] = t_to_orig[(size_t)pl->bt.entry_index[e]];
   } catch (const std::bad_alloc&) {
     pl->bt.packed = false;
     return SWCONV_ENOMEM;
   }
   int rc = upload_packed(&pl->bt);
   if (rc) return rc;
+  if ((rc = upload(&pl->d_bt_value_index, pl->bt_value_index, &pl->cap_bt_value_index))) return rc;
   if (!pl->dD) {
     HIP_TRY(hipMalloc((void**)&pl->dD, pl->g.v_bytes));
     HIP_TRY(hipMemset(pl->dD, 0, pl->g.v_bytes));
@@ -1069,7 +1097,7 @@ void swconv_plan_destroy(swconv_plan* pl) {
     if (b) (void)hipFree(b);
   free_packed(&pl->fw);
   free_packed(&pl->bt);
-  void* fused[] = {pl->fz.d_wpk, pl->fz.d_lens, pl->fz.d_otiles, pl->d_gtiles};
+  void* fused[] = {pl->fz.d_wpk, pl->fz.d_lens, pl->fz.d_otiles, pl->d_gtiles, pl->fz.d_value_index, pl->d_bt_value_index};
   for (void* b : fused)
     if (b) (void)hipFree(b);
   delete pl;
@@ -1082,6 +1110,7 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   size_grid(&pl->fw, (int64_t)pl->P * pl->n_tau_blocks * (pl->fw.rows_padded / kSliceRows));
   pl->bt_current = false;
   pl->index_current = false;
+  pl->host_values_stale = false;
   pl->fz.ready = false;
   try {
     pack_matrix(&pl->fw, pl->P, pl->n_tau_blocks, rowptr, colidx, vals);
@@ -1259,6 +1288,31 @@ int swconv_set_weights_device(swconv_plan* pl, void* hip_stream, const int32_t* 
   }
 }
 
+int swconv_update_values(swconv_plan* pl, void* hip_stream, const float* vals_dev) {
+  if (!pl) return SWCONV_EINVAL;
+  if (!pl->fw.on_device) return SWCONV_ESTATE;
+  if (pl->fw.nnz == 0) return SWCONV_OK;
+  if (!vals_dev) return SWCONV_EINVAL;
+  int rc;
+  if (!pl->index_current) {  // the pair -> CSR index map of W_F (also used by the weight gradient)
+    HIP_TRY(hipDeviceSynchronize());
+    if ((rc = upload(&pl->d_entry_index, pl->fw.entry_index, &pl->cap_entry_index))) return rc;
+    pl->index_current = true;
+  }
+  const LaunchTarget to{(hipStream_t)hip_stream, nullptr, nullptr};
+  auto refresh = [&](uint32_t* pairs, const int32_t* index, size_t n_pairs) {
+    return launch_kernel(refresh_values_kernel, dim3((unsigned)((n_pairs + 255) / 256)), dim3(256), 0, to, pairs, index,
+                         (uint32_t)n_pairs, vals_dev);
+  };
+  if ((rc = refresh(pl->fw.d_stream, pl->d_entry_index, pl->fw.stream.size() / 2))) return rc;
+  if (pl->fz.ready && (rc = refresh(pl->fz.d_wpk, pl->fz.d_value_index, pl->fz.wpk.size() / 2))) return rc;
+  if (pl->bt_current && pl->bt.on_device &&
+      (rc = refresh(pl->bt.d_stream, pl->d_bt_value_index, pl->bt.stream.size() / 2)))
+    return rc;
+  pl->host_values_stale = true;
+  return SWCONV_OK;
+}
+
 int swconv_debug_copy_V(swconv_plan* pl, float* V_host) {
   if (!pl || !V_host) return SWCONV_EINVAL;
   if (!pl->ran_forward) return SWCONV_ESTATE;
@@ -1281,6 +1335,8 @@ int swconv_debug_export_weights(swconv_plan* pl, int32_t* rowptr, int32_t* colid
   if (!pl || !rowptr) return SWCONV_EINVAL;
   if (!pl->fw.packed) return SWCONV_ESTATE;
   if (pl->fw.nnz > 0 && (!colidx || !vals)) return SWCONV_EINVAL;
+  int rc = refresh_host_values(pl);
+  if (rc) return rc;
   unpack_matrix(pl->fw, pl->P, rowptr, colidx, vals);
   return SWCONV_OK;
 }

@@ -84,4 +84,16 @@ __global__ __launch_bounds__(256) void prune_compact_kernel(int64_t rows, const 
   }
 }
 
+// Fine-tuning with the sparsity pattern fixed (Section 4.3): only the values of W_F change.  Every
+// (offset, weight) pair of a packed stream takes its weight from the caller's CSR value array
+// through the pair's index into that array; padding pairs (index -1) keep +0.0f.
+__global__ __launch_bounds__(256) void refresh_values_kernel(uint32_t* __restrict__ pairs,
+                                                             const int32_t* __restrict__ index, uint32_t n_pairs,
+                                                             const float* __restrict__ vals) {
+  const uint32_t e = blockIdx.x * 256u + threadIdx.x;
+  if (e >= n_pairs) return;
+  const int32_t q = index[e];
+  if (q >= 0) pairs[2 * (size_t)e + 1] = __float_as_uint(vals[q]);
+}
+
 }  // namespace swconv

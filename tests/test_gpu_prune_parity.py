@@ -76,3 +76,49 @@ def test_backward_prune_set_weights_forward_round():
         assert np.abs(out.cpu().numpy() - ref).max() <= 1e-4 * np.abs(ref).max()
     finally:
         sw.swconv_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("m,r,C,K,backward_first", [(4, 3, 40, 30, True), (4, 3, 40, 30, False), (2, 5, 24, 70, True),
+                                                     (2, 3, 12, 9, False)])
+def test_update_values_equals_setting_the_weights_anew(m, r, C, K, backward_first):
+    """Fine-tuning step (Section 4.3): new values, same pattern, written in place on the device - every
+    result must be bit-identical to a plan that was given the new values with swconv_set_weights."""
+    N, H, W, pad = 5, 13, 13, r // 2
+    P = (m + r - 1) ** 2
+    rng = np.random.default_rng(8800 + C)
+    x = synth.activations(N, C, H, W, 8801)
+    rp, ci, va1 = synth.bernoulli_weights(P, K, C, 0.3, 8802)
+    va2 = rng.standard_normal(len(va1)).astype(np.float32)
+    G = rng.standard_normal((N, K, 13, 13)).astype(np.float32)
+    xd, gd = torch.from_numpy(x).cuda(), torch.from_numpy(G).cuda()
+
+    def passes(plan):
+        out = torch.full((N, K, 13, 13), float("nan"), device="cuda")
+        din = torch.full((N, C, H, W), float("nan"), device="cuda")
+        dv = torch.full((len(va1),), float("nan"), device="cuda")
+        sw.swconv_forward(plan, 0, xd.data_ptr(), out.data_ptr())
+        sw.swconv_backward(plan, 0, xd.data_ptr(), gd.data_ptr(), din.data_ptr(), dv.data_ptr())
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), din.cpu().numpy(), dv.cpu().numpy()
+
+    ref_plan = sw.swconv_plan_create(N, C, H, W, K, m, r, pad)
+    plan = sw.swconv_plan_create(N, C, H, W, K, m, r, pad)
+    try:
+        sw.swconv_set_weights(ref_plan, rp, ci, va2)
+        want = passes(ref_plan)
+        sw.swconv_set_weights(plan, rp, ci, va1)
+        if backward_first:
+            passes(plan)                       # the transposed weights exist and are updated in place
+        sw.swconv_update_values(plan, 0, torch.from_numpy(va2).cuda().data_ptr())
+        got = passes(plan)                     # otherwise they are built from the updated values
+        for g, w in zip(got, want):
+            np.testing.assert_array_equal(g.view(np.uint32), w.view(np.uint32))
+        rp3, ci3, va3 = sw.swconv_debug_export_weights(plan, K, int(rp[-1]))
+        np.testing.assert_array_equal(rp3, rp)
+        np.testing.assert_array_equal(ci3, ci)
+        np.testing.assert_array_equal(va3.view(np.uint32), va2.view(np.uint32))
+        o64, _, _ = oracle.forward_f64(x, rp, ci, va2, K, m, r, pad, want_VM=False)
+        assert np.abs(got[0] - o64).max() <= 1e-4 * np.abs(o64).max()
+    finally:
+        sw.swconv_plan_destroy(plan)
+        sw.swconv_plan_destroy(ref_plan)
