@@ -69,11 +69,19 @@ def test_backward_prune_set_weights_forward_round():
         np.testing.assert_array_equal(rp2, rp_o)
         np.testing.assert_array_equal(va2.view(np.uint32), va_o.view(np.uint32))
         assert 0 < rp2[-1] < len(va)
-        sw.swconv_set_weights_device(plan, st, dev[0].data_ptr(), dev[1].data_ptr(), dev[2].data_ptr())
+        # without re-packing: the thresholded values in the old pattern (zeros where an entry was dropped)
+        # go into the packed weights in place; dropped entries then multiply as stored zeros
+        sw.swconv_update_values(plan, st, torch.from_numpy(upd).cuda().data_ptr())
+        sw.swconv_forward(plan, st, xd.data_ptr(), out.data_ptr())
+        torch.cuda.synchronize()
+        out_in_place = out.cpu().numpy()
+        # with re-packing: the compacted CSR of the survivors
         sw.swconv_forward(plan, st, xd.data_ptr(), out.data_ptr())
         torch.cuda.synchronize()
         ref = oracle.forward_f64(x, rp_o, ci_o, va_o, K, m, 3, pad, want_VM=False)[0]
         assert np.abs(out.cpu().numpy() - ref).max() <= 1e-4 * np.abs(ref).max()
+        # a stored zero adds exactly nothing to a row sum whose order is otherwise unchanged
+        np.testing.assert_array_equal(out_in_place, out.cpu().numpy())
     finally:
         sw.swconv_plan_destroy(plan)
 
