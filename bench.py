@@ -202,6 +202,14 @@ def main():
         t0 = time.perf_counter()
         sw.swconv_set_weights(plan, rp, ci, va)
         update_weights_ms = (time.perf_counter() - t0) * 1e3   # a weight update: validate, re-pack, schedule, copy
+        vd = torch.from_numpy(va).to(dev)
+        sw.swconv_update_values(plan, sp, vd.data_ptr())
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(100):
+            sw.swconv_update_values(plan, sp, vd.data_ptr())
+        torch.cuda.synchronize()
+        update_values_us = (time.perf_counter() - t0) / 100 * 1e6   # same pattern, new values, in place on the device
         sets = [(plan, xp, op)]
         keep = []
         for _ in range(1, max(1, args.rotate)):
@@ -275,7 +283,8 @@ def main():
         result["stages"] = stages
         st = sw.swconv_plan_weight_stats(plan)
         result["weights"] = {"set_weights_ms": round(set_weights_ms, 3),
-                             "update_weights_ms": round(update_weights_ms, 3), "padded_nnz": st["padded_nnz"],
+                             "update_weights_ms": round(update_weights_ms, 3),
+                             "update_values_us": round(update_values_us, 2), "padded_nnz": st["padded_nnz"],
                              "work_items": st["work_items"]}
 
     if not args.no_cpu_baseline:
