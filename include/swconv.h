@@ -64,7 +64,7 @@ typedef struct swconv_plan swconv_plan; /* opaque, owned by the library */
 typedef enum {
   SWCONV_OK = 0,
   SWCONV_EINVAL = 1,       /* bad shape, null pointer, malformed CSR                 */
-  SWCONV_EUNSUPPORTED = 2, /* (m,r) other than (2,3),(4,3); sizes beyond the kernels */
+  SWCONV_EUNSUPPORTED = 2, /* an F(m,r) that is not built; sizes beyond the kernels   */
   SWCONV_ENOMEM = 3,       /* host or device allocation failed                       */
   SWCONV_EHIP = 4,         /* HIP runtime error (no device, launch failure, ...)     */
   SWCONV_ESTATE = 5        /* forward before weights were set                        */
