@@ -98,7 +98,9 @@ void swconv_plan_destroy(swconv_plan* plan);
  * The arrays are validated, re-packed into the kernels' sliced layout (rows of a position
  * sorted by length, grouped four at a time, padded with zero weights) together with a
  * static, cost-balanced schedule for the persistent workgroups of the sparse product, and copied
- * to the device before the call returns; the caller keeps ownership of its arrays.  May be called again with a new pattern.  Blocks the host.
+ * to the device before the call returns; the caller keeps ownership of its arrays.  May be called
+ * again with a new pattern; what the workspaces hold then counts as stale (swconv_debug_copy_V / _M and a
+ * swconv_backward with in_dev = NULL return ESTATE until the next forward pass).  Blocks the host.
  * Errors: EINVAL on any CSR violation (the plan keeps its previous weights); ENOMEM; EHIP when
  * no device is usable - the host-side packed copy is still kept in that case, so
  * swconv_debug_export_weights works without a GPU.

@@ -1112,6 +1112,10 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   pl->index_current = false;
   pl->host_values_stale = false;
   pl->fz.ready = false;
+  // what the workspaces hold belongs to the old weights: the products are stale, and a backward pass
+  // must not pair I_F of an earlier pass with the new pattern without a forward pass in between
+  pl->m_current = false;
+  pl->ran_forward = false;
   try {
     pack_matrix(&pl->fw, pl->P, pl->n_tau_blocks, rowptr, colidx, vals);
     pack_fused(pl, rowptr, colidx, vals);

@@ -29,7 +29,7 @@ CONFIGS = {
     "alexnet_conv2g_n32_f4r5": dict(N=32, C=48, H=27, W=27, K=128, m=4, r=5, pad=2, density=0.094, seed=BASE_SEED + 8),
     "conv4_skewed_n64_f4": dict(N=64, C=384, H=13, W=13, K=384, m=4, r=3, pad=1, density=None, seed=BASE_SEED + 6),
 }
-BENCH_CONFIG = "alexnet_conv3_n32_f4"
+BENCH_CONFIG = "vgg_56_n32_f4"
 DENSITY_SWEEP = (0.30, 0.20, 0.10, 0.05)
 
 

@@ -128,6 +128,19 @@ def test_backward_can_reuse_the_forward_pass_transform():
         assert relerr(dv.cpu().numpy(), dvals64) <= RTOL[m]
         with pytest.raises(sw.SwconvError):          # the backward pass used the workspace
             sw.swconv_backward(plan, 0, 0, gd.data_ptr(), din.data_ptr(), dv.data_ptr())
+        # new weights: what the workspaces hold belongs to the old ones until a forward pass has run
+        sw.swconv_forward(plan, 0, xd.data_ptr(), out.data_ptr())
+        sw.swconv_set_weights(plan, rp, ci, va)
+        with pytest.raises(sw.SwconvError) as e:
+            sw.swconv_backward(plan, 0, 0, gd.data_ptr(), din.data_ptr(), dv.data_ptr())
+        assert e.value.status == sw.SWCONV_ESTATE
+        with pytest.raises(sw.SwconvError) as e:
+            sw.swconv_debug_copy_M(plan, K)
+        assert e.value.status == sw.SWCONV_ESTATE
+        sw.swconv_forward(plan, 0, xd.data_ptr(), out.data_ptr())
+        sw.swconv_backward(plan, 0, 0, gd.data_ptr(), din.data_ptr(), dv.data_ptr())
+        torch.cuda.synchronize()
+        assert relerr(dv.cpu().numpy(), dvals64) <= RTOL[m]
     finally:
         sw.swconv_plan_destroy(plan)
 

@@ -191,9 +191,11 @@ def test_full_size_configs(name):
                          stages=(cfg["N"] <= 32))
 
 
-@pytest.mark.parametrize("density", [0.30, 0.05])
-def test_density_sweep_conv3(density):
-    cfg, x, rp, ci, va = synth.make_layer("alexnet_conv3_n64_f4", density=density)
+@pytest.mark.parametrize("density", synth.DENSITY_SWEEP)
+@pytest.mark.parametrize("name", ["alexnet_conv3_n64_f4", "alexnet_conv4_n64_f4", "alexnet_conv5_n64_f4"])
+def test_density_sweep(name, density):
+    # the three 3x3 layers at batch 64, each at every density of the sweep (Table 1's sparsity range)
+    cfg, x, rp, ci, va = synth.make_layer(name, density=density)
     check_against_oracle(cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"], cfg["m"], cfg["pad"], x, rp, ci, va,
                          stages=False)
 
