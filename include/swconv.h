@@ -127,6 +127,30 @@ int swconv_set_weights(swconv_plan* plan, const int32_t* rowptr, const int32_t* 
 int swconv_forward(swconv_plan* plan, void* hip_stream, const float* in_dev, float* out_dev);
 
 /*
+ * swconv_forward for callers that cannot allocate device memory and do not want every plan to hold
+ * workspaces of its own: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The same kernels as swconv_forward, with the two intermediates (V, then M on the
+ * next 256-byte boundary) in a static device array of SWCONV_STATIC_SCRATCH_BYTES (64 MiB) that
+ * the library's code object carries: every GPU the library runs on holds one copy until the
+ * process ends, and all plans share it.  The call allocates and frees nothing and calls no
+ * allocating routine; the array's device address is looked up once per device (by the first
+ * swconv_set_weights on that device, else by the first call here).  Arguments, asynchrony and
+ * results as for swconv_forward: the output is bit-identical to it.
+ * Limits: 4*P*(C+K)*Tp bytes (Tp = T rounded up to 128), rounded as above, must fit the array -
+ * e.g. the N = 32, 256 -> 384, 13 x 13, F(4x4,3x3) layer (47.2 MB) does, N = 64 does not:
+ * SWCONV_EUNSUPPORTED, nothing is launched.  Calls on one GPU share the array, whatever their
+ * plans or streams: two calls that overlap in time race; order them on one stream or with events.
+ * The array keeps the last call's contents, and nothing in it has to start at zero (step 1
+ * writes every column of V and step 2 every row of M that a later step reads).  The plan's own
+ * workspaces are untouched, so swconv_debug_copy_V / _M and a swconv_backward with in_dev = NULL
+ * return ESTATE until a swconv_forward has run.
+ * Errors: EINVAL (null), ESTATE (no weights), EUNSUPPORTED (too large; more than 64 devices),
+ * EHIP (symbol lookup or launch failure).
+ */
+#define SWCONV_STATIC_SCRATCH_BYTES (64u << 20)
+int swconv_forward_noalloc(swconv_plan* plan, void* hip_stream, const float* in_dev, float* out_dev);
+
+/*
  * The 0 %-sparsity comparison: the same layer with a dense W_F, computed with the same
  * transforms and a dense batched fp32 MFMA product for step 2.  Not the paper's method - the
  * paper has no dense Winograd implementation and projects one (Section 6.2); this is the

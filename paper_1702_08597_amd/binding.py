@@ -19,7 +19,7 @@ EXPORTS = [
     "swconv_plan_weight_stats", "swconv_debug_check_schedule",
     "swconv_backward", "swconv_debug_copy_dZ", "swconv_debug_copy_dV", "swconv_profile_backward",
     "swconv_prune_step", "swconv_set_weights_device", "swconv_plan_set_image_strides",
-    "swconv_update_values",
+    "swconv_update_values", "swconv_forward_noalloc",
 ]
 
 _lib = None
@@ -48,6 +48,7 @@ def lib():
         L.swconv_plan_destroy.restype = None
         L.swconv_set_weights.argtypes = [_vp, _i32p, _i32p, _f32p]
         L.swconv_forward.argtypes = [_vp, _vp, _vp, _vp]
+        L.swconv_forward_noalloc.argtypes = [_vp, _vp, _vp, _vp]
         L.swconv_set_weights_dense.argtypes = [_vp, _f32p]
         L.swconv_forward_dense.argtypes = [_vp, _vp, _vp, _vp]
         L.swconv_profile_forward.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_int, _f32p]
@@ -115,6 +116,11 @@ def swconv_set_weights_status(plan, rowptr, colidx, vals):
 def swconv_forward(plan, stream, in_dev_ptr, out_dev_ptr):
     """stream: hipStream_t as int (0 = default); in/out: device addresses as int."""
     _check(lib().swconv_forward(plan, _vp(stream), _vp(in_dev_ptr), _vp(out_dev_ptr)), "swconv_forward")
+
+
+def swconv_forward_noalloc(plan, stream, in_dev_ptr, out_dev_ptr):
+    """swconv_forward with the intermediates in the library's static device scratch (no allocation)."""
+    _check(lib().swconv_forward_noalloc(plan, _vp(stream), _vp(in_dev_ptr), _vp(out_dev_ptr)), "swconv_forward_noalloc")
 
 
 def swconv_backward(plan, stream, in_dev_ptr, dout_dev_ptr, din_dev_ptr, dvals_dev_ptr):

@@ -10,6 +10,7 @@
 #include <cstring>
 #include <new>
 #include <atomic>
+#include <mutex>
 #include <numeric>
 #include <thread>
 #include <type_traits>
@@ -180,7 +181,40 @@ struct swconv_plan {
   float* d_wdense = nullptr;  // [P][C][Kq]
 };
 
+// Scratch of swconv_forward_noalloc: the V and M workspaces of one forward pass, for callers that
+// cannot allocate.  One copy per GPU the library runs on, held until the process ends.  In host code
+// the array's name only stands for the symbol: the memory is reached through the per-device address
+// that static_scratch() asks the runtime for, never through the name.
+constexpr size_t kStaticScratchBytes = SWCONV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_of_device[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch` (looked up once per device).
+int static_scratch(void** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SWCONV_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_of_device[dev]) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return SWCONV_EHIP;
+    scratch_of_device[dev] = ptr;
+  }
+  *out = scratch_of_device[dev];
+  return SWCONV_OK;
+}
+
+// The two intermediates of a forward pass: the plan's own buffers, or parts of the static scratch.
+struct Workspace {
+  float* V;
+  float* M;
+};
 
 int ensure_workspace(swconv_plan* pl) {
   if (pl->on_device) return SWCONV_OK;
@@ -197,6 +231,9 @@ int ensure_workspace(swconv_plan* pl) {
   int rc;
   if ((rc = upload(&pl->d_tiles, pl->tiles))) return rc;
   if ((rc = upload(&pl->d_blocks, pl->blocks))) return rc;
+  // set-up time: look up this device's static scratch now, so that swconv_forward_noalloc finds it known
+  void* unused = nullptr;
+  (void)static_scratch(&unused);
   pl->on_device = true;
   return SWCONV_OK;
 }
@@ -230,7 +267,7 @@ int dispatch_mr(const swconv_plan* pl, F&& f) {
 }
 
 template <int M, int R>
-int launch_input_transform(const swconv_plan* pl, const LaunchTarget& to, const float* in) {
+int launch_input_transform(const swconv_plan* pl, const LaunchTarget& to, const float* in, float* V) {
   dim3 grid(pl->g.Tp / 64, (pl->g.C + 3) / 4);
   const size_t lds = (size_t)4 * pl->g.in_area * sizeof(float);
   auto kern = input_transform_kernel<M, R>;
@@ -239,11 +276,11 @@ int launch_input_transform(const swconv_plan* pl, const LaunchTarget& to, const 
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  return launch_kernel(kern, grid, dim3(256), lds, to, in, pl->dV, pl->d_tiles, pl->d_blocks, pl->g);
+  return launch_kernel(kern, grid, dim3(256), lds, to, in, V, pl->d_tiles, pl->d_blocks, pl->g);
 }
 
 template <int M, int R>
-int launch_output_transform(const swconv_plan* pl, const LaunchTarget& to, float* out) {
+int launch_output_transform(const swconv_plan* pl, const LaunchTarget& to, const float* Mbuf, float* out) {
   dim3 grid(pl->g.Tp / 64, (pl->g.K + 3) / 4);
   const size_t lds = (size_t)4 * pl->g.out_area * sizeof(float);
   auto kern = output_transform_kernel<M, R>;
@@ -252,7 +289,7 @@ int launch_output_transform(const swconv_plan* pl, const LaunchTarget& to, float
     HIP_TRY(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsBytes));
     attr_set = true;
   }
-  return launch_kernel(kern, grid, dim3(256), lds, to, pl->dM, out, pl->d_tiles, pl->d_blocks, pl->g);
+  return launch_kernel(kern, grid, dim3(256), lds, to, Mbuf, out, pl->d_tiles, pl->d_blocks, pl->g);
 }
 
 // Y[p] = A[p] * X[p] for the packed operand `pm`: X has pm.cols rows of Tp tiles per position and
@@ -289,7 +326,7 @@ int launch_spmm(const swconv_plan* pl, const PackedMatrix& pm, const LaunchTarge
 }
 
 template <int R, int PP>
-int launch_product_output_t(const swconv_plan* pl, const LaunchTarget& to, float* out) {
+int launch_product_output_t(const swconv_plan* pl, const LaunchTarget& to, const float* V, float* out) {
   const FusedProduct& fz = pl->fz;
   const Geometry& g = pl->g;
   const size_t lds = (size_t)2 * ((size_t)g.C * kTileBlock * sizeof(float) + (size_t)kFusedWaves * fz.B * 512) + 1024;
@@ -300,18 +337,18 @@ int launch_product_output_t(const swconv_plan* pl, const LaunchTarget& to, float
     attr_set = true;
   }
   const int n_wgs = pl->n_tau_blocks * fz.KC;
-  return launch_kernel(kern, dim3(n_wgs), dim3(kFusedWaves * 64), lds, to, (const float*)pl->dV, out,
+  return launch_kernel(kern, dim3(n_wgs), dim3(kFusedWaves * 64), lds, to, V, out,
                        (const uint32_t*)fz.d_wpk, (uint32_t)(fz.wpk.size() * sizeof(uint32_t)),
                        (const uint8_t*)fz.d_lens, (const OutTile*)fz.d_otiles, g.C, g.K, g.Tp, fz.KC, fz.B, n_wgs,
                        g.v_bytes, (uint32_t)(g.Ho * g.Wo), g.Wo, (uint32_t)g.out_image_stride,
                        (uint32_t)((int64_t)g.N * g.out_image_stride * (int64_t)sizeof(float)));
 }
 
-int launch_product_output(const swconv_plan* pl, const LaunchTarget& to, float* out) {
+int launch_product_output(const swconv_plan* pl, const LaunchTarget& to, const float* V, float* out) {
   const bool one_piece = pl->g.C * (kTileBlock / 4) <= kFusedWaves * 64;
   if (pl->r == 3)
-    return one_piece ? launch_product_output_t<3, 1>(pl, to, out) : launch_product_output_t<3, 2>(pl, to, out);
-  return one_piece ? launch_product_output_t<5, 1>(pl, to, out) : launch_product_output_t<5, 2>(pl, to, out);
+    return one_piece ? launch_product_output_t<3, 1>(pl, to, V, out) : launch_product_output_t<3, 2>(pl, to, V, out);
+  return one_piece ? launch_product_output_t<5, 1>(pl, to, V, out) : launch_product_output_t<5, 2>(pl, to, V, out);
 }
 
 // The forward pass is three kernels, or two where steps 2 and 3 run fused.
@@ -321,15 +358,19 @@ bool fused_runs(const swconv_plan* pl) {
 }
 bool forward_stage_runs(const swconv_plan* pl, int stage) { return stage < 2 || !fused_runs(pl); }
 
-int launch_stage(const swconv_plan* pl, const LaunchTarget& to, int stage, const float* in, float* out) {
-  if (stage == 1 && fused_runs(pl)) return launch_product_output(pl, to, out);
+int launch_stage(const swconv_plan* pl, const LaunchTarget& to, int stage, const float* in, float* out,
+                 const Workspace& ws) {
+  if (stage == 1 && fused_runs(pl)) return launch_product_output(pl, to, ws.V, out);
   switch (stage) {
     case 0:
-      return dispatch_mr(pl, [&](auto M, auto R) { return launch_input_transform<M(), R()>(pl, to, in); });
-    case 1: return launch_spmm(pl, pl->fw, to, pl->dV, pl->g.v_bytes, pl->dM, pl->g.m_bytes);
+      return dispatch_mr(pl, [&](auto M, auto R) { return launch_input_transform<M(), R()>(pl, to, in, ws.V); });
+    case 1: return launch_spmm(pl, pl->fw, to, ws.V, pl->g.v_bytes, ws.M, pl->g.m_bytes);
     default:
-      return dispatch_mr(pl, [&](auto M, auto R) { return launch_output_transform<M(), R()>(pl, to, out); });
+      return dispatch_mr(pl, [&](auto M, auto R) { return launch_output_transform<M(), R()>(pl, to, ws.M, out); });
   }
+}
+int launch_stage(const swconv_plan* pl, const LaunchTarget& to, int stage, const float* in, float* out) {
+  return launch_stage(pl, to, stage, in, out, Workspace{pl->dV, pl->dM});
 }
 
 // Index tables of the two transform kernels: where each tile and each (tile block, image) part
@@ -1141,6 +1182,29 @@ int swconv_forward(swconv_plan* pl, void* hip_stream, const float* in_dev, float
   }
   pl->ran_forward = true;
   pl->m_current = !fused_runs(pl);
+  return SWCONV_OK;
+}
+
+int swconv_forward_noalloc(swconv_plan* pl, void* hip_stream, const float* in_dev, float* out_dev) {
+  if (!pl || !in_dev || !out_dev) return SWCONV_EINVAL;
+  if (!pl->fw.on_device) return SWCONV_ESTATE;
+  // V, then M behind it on a 256-byte boundary
+  const size_t m_at = ((size_t)pl->g.v_bytes + 255) / 256 * 256;
+  if (m_at + (size_t)pl->g.m_bytes > kStaticScratchBytes) return SWCONV_EUNSUPPORTED;
+  void* base = nullptr;
+  int rc = static_scratch(&base);
+  if (rc) return rc;
+  const Workspace ws{reinterpret_cast<float*>(base), reinterpret_cast<float*>(static_cast<unsigned char*>(base) + m_at)};
+  const LaunchTarget to{(hipStream_t)hip_stream, nullptr, nullptr};
+  // Nothing in the scratch has to start at zero: step 1 writes every column of V the later steps
+  // read (the pad columns included), step 2 every row of M that step 3 reads.
+  for (int stage = 0; stage < 3; ++stage) {
+    if (!forward_stage_runs(pl, stage)) continue;
+    if ((rc = launch_stage(pl, to, stage, in_dev, out_dev, ws))) return rc;
+  }
+  // the plan's own workspaces hold nothing of this pass
+  pl->ran_forward = false;
+  pl->m_current = false;
   return SWCONV_OK;
 }
 
