@@ -115,6 +115,9 @@ int swconv_set_weights(swconv_plan* plan, const int32_t* rowptr, const int32_t* 
  * ONE kernel that keeps the per-position products on chip (Section 5: a core that owns its
  * tiles through all steps can fuse the second and third); the environment variable
  * SWCONV_FUSE_OUTPUT=0, read by swconv_plan_create, keeps such a plan on three kernels.
+ * SWCONV_FUSE_OUTPUT=2 also runs F(4x4,3x3) layers with C a multiple of 4, C <= 256 and rows of
+ * at most 224 stored entries through a fused kernel of their own (measured slower than the two
+ * kernels on the layers tried, hence not the default).
  *   in_dev   DEVICE, N x C x H x W fp32, contiguous (W fastest), read-only.
  *   out_dev  DEVICE, N x K x Ho x Wo fp32, contiguous; every element is overwritten.
  * The two must not alias and must live on the device the weights were set on.  The plan owns

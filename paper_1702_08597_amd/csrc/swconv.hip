@@ -126,6 +126,9 @@ struct PackedMatrix {
 // W_F packed for the fused product + output transform kernel (m = 2, few input channels): rows in
 // their natural order, 64 per workgroup, one package of 16-step batches per position.
 struct FusedProduct {
+  int out_tile = 0;       // m of the kernel that would run: 2 (product_output_kernel) or 4 (product_output4_kernel)
+  int mode = 1;           // SWCONV_FUSE_OUTPUT: 0 never, 1 where it pays (m = 2), 2 wherever a kernel can run
+  bool wanted = true;     // m = 2: always; m = 4: only when asked for through SWCONV_FUSE_OUTPUT=2
   bool eligible = false;  // the layer shape allows the kernel
   bool ready = false;     // the current weights fit its format and are on the device
   int KC = 0;             // row chunks of kFusedRows
@@ -351,16 +354,37 @@ int launch_product_output(const swconv_plan* pl, const LaunchTarget& to, const f
   return one_piece ? launch_product_output_t<5, 1>(pl, to, V, out) : launch_product_output_t<5, 2>(pl, to, V, out);
 }
 
+template <int G>
+int launch_product_output4_t(const swconv_plan* pl, const LaunchTarget& to, const float* V, float* out) {
+  const FusedProduct& fz = pl->fz;
+  const int n_wgs = pl->n_tau_blocks * fz.KC;
+  return launch_kernel(product_output4_kernel<3, G>, dim3(n_wgs), dim3(kFusedWaves * 64), 0, to, V, out,
+                       (const uint32_t*)fz.d_wpk, (uint32_t)(fz.wpk.size() * sizeof(uint32_t)),
+                       (const uint8_t*)fz.d_lens, (const TileInfo*)pl->d_tiles, (const BlockImage*)pl->d_blocks, fz.KC,
+                       fz.B, n_wgs, pl->g);
+}
+
+int launch_product_output4(const swconv_plan* pl, const LaunchTarget& to, const float* V, float* out) {
+  switch ((pl->g.C + 63) / 64) {  // direct loads per wave and panel
+    case 1: return launch_product_output4_t<1>(pl, to, V, out);
+    case 2: return launch_product_output4_t<2>(pl, to, V, out);
+    case 3: return launch_product_output4_t<3>(pl, to, V, out);
+    default: return launch_product_output4_t<4>(pl, to, V, out);
+  }
+}
+
 // The forward pass is three kernels, or two where steps 2 and 3 run fused.
 bool fused_runs(const swconv_plan* pl) {
   // its output stores use 32-bit byte offsets from the output pointer
-  return pl->fz.ready && (int64_t)pl->g.N * pl->g.out_image_stride * (int64_t)sizeof(float) < ((int64_t)1 << 32) - 256;
+  return pl->fz.ready && pl->fz.wanted &&
+         (int64_t)pl->g.N * pl->g.out_image_stride * (int64_t)sizeof(float) < ((int64_t)1 << 32) - 256;
 }
 bool forward_stage_runs(const swconv_plan* pl, int stage) { return stage < 2 || !fused_runs(pl); }
 
 int launch_stage(const swconv_plan* pl, const LaunchTarget& to, int stage, const float* in, float* out,
                  const Workspace& ws) {
-  if (stage == 1 && fused_runs(pl)) return launch_product_output(pl, to, ws.V, out);
+  if (stage == 1 && fused_runs(pl))
+    return pl->fz.out_tile == 4 ? launch_product_output4(pl, to, ws.V, out) : launch_product_output(pl, to, ws.V, out);
   switch (stage) {
     case 0:
       return dispatch_mr(pl, [&](auto M, auto R) { return launch_input_transform<M(), R()>(pl, to, in, ws.V); });
@@ -423,7 +447,7 @@ void build_transform_tables(swconv_plan* pl) {
         ti.yx0 = (int32_t)(((uint32_t)y0 & 0xffffu) | ((uint32_t)x0 << 16));
         ti.ylim = (int32_t)((uint32_t)y_lo | ((uint32_t)(y_hi - 1) << 16));
         ti.out_org = bi.out_off + (ty * m - oy_lo) * g.Wo + tx * m;
-        if (pl->fz.eligible) {
+        if (!pl->fz.otiles.empty()) {
           OutTile& ot = pl->fz.otiles[(size_t)base + tl];
           ot.n = (uint32_t)n;
           ot.pix = (uint32_t)(ty * m * g.Wo + tx * m);
@@ -442,11 +466,13 @@ void pack_fused(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, c
   fz.ready = false;
   if (!fz.eligible) return;
   const int P = pl->P, K = pl->g.K;
+  const bool units = fz.out_tile == 4;  // F(4x4,3x3): whole units of two batches
   int32_t longest = 0;
   for (int64_t i = 0; i < (int64_t)P * K; ++i) longest = std::max(longest, rowptr[i + 1] - rowptr[i]);
   fz.KC = (K + kFusedRows - 1) / kFusedRows;
   fz.B = std::max(1, (longest + kBatchSteps - 1) / kBatchSteps);
-  if (fz.B > kFusedMaxBatches) return;
+  if (units) fz.B = (fz.B + 1) / 2 * 2;
+  if (fz.B > (units ? kFused4MaxBatches : kFusedMaxBatches)) return;
   const int spp = fz.KC * kFusedWaves;
   const size_t dwords = (size_t)P * fz.KC * fz.B * kFusedWaves * 128;
   if (dwords * 4 >= ((size_t)1 << 32) - 4096) return;
@@ -454,12 +480,17 @@ void pack_fused(swconv_plan* pl, const int32_t* rowptr, const int32_t* colidx, c
   fz.value_index.assign(dwords / 2, -1);
   fz.lens.assign((size_t)P * spp, 0);
   const uint32_t row_bytes = (uint32_t)kTileBlock * sizeof(float);
+  // steps of every slice: its longest row, rounded up to whole groups of steps
+  for (int p = 0; p < P; ++p)
+    for (int k = 0; k < K; ++k) {
+      const int32_t len = rowptr[(int64_t)p * K + k + 1] - rowptr[(int64_t)p * K + k];
+      uint8_t& steps = fz.lens[(size_t)p * spp + k / kSliceRows];
+      steps = std::max<uint8_t>(steps, (uint8_t)((len + kStepGroup - 1) / kStepGroup * kStepGroup));
+    }
   for (int p = 0; p < P; ++p)
     for (int k = 0; k < K; ++k) {
       const int sl = k / kSliceRows, q = k % kSliceRows, kc = sl / kFusedWaves, w = sl % kFusedWaves;
       const int32_t q0 = rowptr[(int64_t)p * K + k], len = rowptr[(int64_t)p * K + k + 1] - q0;
-      uint8_t& steps = fz.lens[(size_t)p * spp + sl];
-      steps = std::max<uint8_t>(steps, (uint8_t)((len + kStepGroup - 1) / kStepGroup * kStepGroup));
       for (int32_t e = 0; e < len; ++e) {
         const size_t batch = (((size_t)p * fz.KC + kc) * fz.B + e / kBatchSteps) * kFusedWaves + w;
         uint32_t* entry = &fz.wpk[batch * 128 + ((size_t)q * kBatchSteps + e % kBatchSteps) * 2];
@@ -479,7 +510,7 @@ int upload_fused(swconv_plan* pl) {
   if ((rc = upload(&fz.d_wpk, fz.wpk, &fz.cap_wpk))) return rc;
   if ((rc = upload(&fz.d_lens, fz.lens, &fz.cap_lens))) return rc;
   if ((rc = upload(&fz.d_value_index, fz.value_index, &fz.cap_value_index))) return rc;
-  if (!fz.d_otiles && (rc = upload(&fz.d_otiles, fz.otiles))) return rc;
+  if (!fz.d_otiles && !fz.otiles.empty() && (rc = upload(&fz.d_otiles, fz.otiles))) return rc;
   HIP_TRY(hipDeviceSynchronize());
   fz.ready = true;
   return SWCONV_OK;
@@ -1071,15 +1102,22 @@ int swconv_plan_create(swconv_plan** out, int N, int C, int H, int W, int K, int
   g.out_image_stride = (int64_t)K * Ho * Wo;
   // steps 2 and 3 in one kernel: m = 2 (16 output accumulators per lane) and a panel of at most
   // kFusedMaxPieces 16-byte pieces per thread
-  pl->fz.eligible = m == 2 && C * (kTileBlock / 4) <= kFusedMaxPieces * kFusedWaves * 64 &&
-                    env_int("SWCONV_FUSE_OUTPUT", 1) != 0;
+  // or F(4x4,3x3) with two C x 64 panels in LDS and whole groups of four panel rows
+  const int fuse_mode = env_int("SWCONV_FUSE_OUTPUT", 1);
+  pl->fz.out_tile = m;
+  pl->fz.mode = fuse_mode;
+  if (m == 2)
+    pl->fz.eligible = C * (kTileBlock / 4) <= kFusedMaxPieces * kFusedWaves * 64 && fuse_mode != 0;
+  else
+    pl->fz.eligible = r == 3 && C % 4 == 0 && C <= kFused4MaxC && fuse_mode != 0;  // and its staging area, see below
   try {
-    if (pl->fz.eligible) pl->fz.otiles.assign((size_t)g.Tp, OutTile{0, 0u, 0u, 0u});
+    if (pl->fz.eligible && m == 2) pl->fz.otiles.assign((size_t)g.Tp, OutTile{0, 0u, 0u, 0u});
     build_transform_tables(pl);
   } catch (const std::bad_alloc&) {
     delete pl;
     return SWCONV_ENOMEM;
   }
+  if (m == 4 && g.out_area > kFused4MaxOutArea) pl->fz.eligible = false;  // output rows of a tile block: staged per wave
   // backward pass, Eq. 6 second and third line in one kernel: G = 64 / (tiles per image) whole
   // images per wave (at least one), if four waves' planes fit LDS
   {
@@ -1160,6 +1198,10 @@ int swconv_set_weights(swconv_plan* pl, const int32_t* rowptr, const int32_t* co
   try {
     pack_matrix(&pl->fw, pl->P, pl->n_tau_blocks, rowptr, colidx, vals);
     pack_fused(pl, rowptr, colidx, vals);
+    // The F(4x4,3x3) kernel runs only where asked for (SWCONV_FUSE_OUTPUT=2): with 64 + 16 accumulators per
+    // lane it holds 16 waves per CU, its vector ALU stays at about two thirds busy between the barriers of
+    // the 36 positions, and on the 56 x 56 layer it measured 217 us against 188 us for the two kernels.
+    pl->fz.wanted = pl->fz.out_tile == 2 || pl->fz.mode == 2;
   } catch (const std::bad_alloc&) {
     pl->fw.packed = false;
     pl->fw.on_device = false;

@@ -181,4 +181,303 @@ __global__ __launch_bounds__(kFusedWaves * 64) void product_output_kernel(
   store_tile(o3, y00.a3, y01.a3, y10.a3, y11.a3);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Steps 2 and 3 in one kernel for F(4x4,3x3) (t = 6, P = 36, 16 outputs per tile and row).
+//
+// Same decomposition as above - a workgroup of 16 waves owns one 64-tile block and 64 rows of W_F
+// through all 36 positions, a wave four rows, a lane one row and four tiles - with the memory side
+// rebuilt around the register file: the lane's 4 x 16 output accumulators and the 16 row sums take
+// 80 of the 128 vector registers a wave has at 16 waves per CU.
+//   - The C x 64 panel of a position goes from memory straight into LDS (16-byte direct loads:
+//     the 64 lanes of a load fill 1024 consecutive bytes of LDS = four panel rows), two panel
+//     buffers, one barrier per position: the panel of position p + 1 arrives while p is computed.
+//     The two buffers are two separate arrays, which is what lets the compiler see that work on
+//     one never has to wait for a direct load into the other.
+//   - The weights do not pass through LDS: a lane fetches its own (row offset, weight) pairs, 16
+//     steps per load.  Two sets of two batch registers in turn: while a position runs on one set,
+//     the other receives the first two batches of the next position, a whole position ahead.
+//   - Inner loop: the steps of a slice run as one rolling pipeline - the panel read of step s + 4
+//     is issued right after the multiply-adds of step s, so a wave always has four LDS reads in
+//     flight.  With the waves of a workgroup re-aligned by the barrier of every position, reads
+//     issued group by group would leave LDS idle while all waves multiply and the vector ALU idle
+//     while all wait.  A unit of the pipeline is two batches (32 steps), written in assembly
+//     with fixed registers for the four reads in flight, and left after the slice's last group of
+//     four steps.
+//   - The fold Y += A^T[.][i] (x) sum_j A^T[.][j] M[(i,j)] runs per position on the lane's four
+//     values (column factor) and once per row of positions (row factor).
+//   - Epilogue: the 4 x 4 outputs go through LDS (the panels are done with) into the layout of the
+//     output rows, one row of W_F at a time per wave, and leave as whole rows with lane-contiguous
+//     stores, as in the stand-alone output transform.
+// M (36 floats per output tile and row; 16 are stored) never exists in memory.
+//
+// Requires C % 4 == 0 (a direct load covers four whole rows), C <= 256 (the two panel arrays) and
+// an output staging area of at most 2048 floats per wave.  G = ceil(C / 64) direct loads per wave
+// and panel; a wave with fewer row groups than G repeats the panel's first group.
+// Weight packages: wpk[p][kc][b][wave], B batches per slice and position (B even: whole units);
+// lens[p][kc*16 + wave] = steps of the slice (a multiple of 4).
+
+constexpr int kFused4MaxBatches = 14;  // steps of a slice must fit the 8-bit length table
+constexpr int kFused4MaxC = 256;       // rows of a panel array
+constexpr int kFused4MaxOutArea = kFused4MaxC * kTileBlock / (kFusedWaves / 2);  // floats per wave: eight waves per array
+constexpr int kUnitSteps = 2 * kBatchSteps;
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+// The first `steps` (a multiple of four, 4 .. 32, wave-uniform) step slots of one unit: slot s takes
+// its (row offset, weight) pair from lane s % 16 of the lane's quarter, in (o0, w0) for s < 16 and
+// (o1, w1) above, reads the 16 bytes at LDS address `lane_base` + row offset and adds weight times
+// those four values to acc.  Rolling pipeline: the reads of slots 0 .. 3 go out first; after the
+// multiply-adds of slot s the read of slot s + 4 is issued into the registers slot s has just
+// released (v[112:127], four registers per read in flight); the last group only multiplies.
+// LDS returns a wave's reads in order, so "all but the three youngest" is the wait for the oldest.
+// A row broadcast operand (DPP) must not follow a vector-ALU write of the same register within two
+// wait states: the pairs are only ever written by memory loads, and the block starts with two.
+#define SWCONV_X0 "v[112:115]"
+#define SWCONV_X1 "v[116:119]"
+#define SWCONV_X2 "v[120:123]"
+#define SWCONV_X3 "v[124:127]"
+#define SWCONV_DPP(N) " row_newbcast:" #N " row_mask:0xf bank_mask:0xf\n"
+#define SWCONV_FMA4(W, N, A, B, C, D)                          \
+  "v_fmac_f32_dpp %[a0], " W ", " A SWCONV_DPP(N)              \
+  "v_fmac_f32_dpp %[a1], " W ", " B SWCONV_DPP(N)              \
+  "v_fmac_f32_dpp %[a2], " W ", " C SWCONV_DPP(N)              \
+  "v_fmac_f32_dpp %[a3], " W ", " D SWCONV_DPP(N)
+#define SWCONV_READ(O, N, XT, XA) "v_add_u32_dpp " XA ", " O ", %[lb]" SWCONV_DPP(N) "ds_read_b128 " XT ", " XA "\n"
+// one group of four slots that is not the slice's last: multiply-adds of lanes N0 .. N3 (weights in W),
+// then the reads of lanes M0 .. M3 (offsets in O)
+#define SWCONV_GROUP_ROLL(W, O, N0, N1, N2, N3, M0, M1, M2, M3)                                            \
+  "s_waitcnt lgkmcnt(3)\n" SWCONV_FMA4(W, N0, "v112", "v113", "v114", "v115") SWCONV_READ(O, M0, SWCONV_X0, "v112") \
+  "s_waitcnt lgkmcnt(3)\n" SWCONV_FMA4(W, N1, "v116", "v117", "v118", "v119") SWCONV_READ(O, M1, SWCONV_X1, "v116") \
+  "s_waitcnt lgkmcnt(3)\n" SWCONV_FMA4(W, N2, "v120", "v121", "v122", "v123") SWCONV_READ(O, M2, SWCONV_X2, "v120") \
+  "s_waitcnt lgkmcnt(3)\n" SWCONV_FMA4(W, N3, "v124", "v125", "v126", "v127") SWCONV_READ(O, M3, SWCONV_X3, "v124")
+// the slice's last group: the pipeline drains
+#define SWCONV_GROUP_LAST(W, N0, N1, N2, N3)                                       \
+  "s_waitcnt lgkmcnt(3)\n" SWCONV_FMA4(W, N0, "v112", "v113", "v114", "v115")      \
+  "s_waitcnt lgkmcnt(2)\n" SWCONV_FMA4(W, N1, "v116", "v117", "v118", "v119")      \
+  "s_waitcnt lgkmcnt(1)\n" SWCONV_FMA4(W, N2, "v120", "v121", "v122", "v123")      \
+  "s_waitcnt lgkmcnt(0)\n" SWCONV_FMA4(W, N3, "v124", "v125", "v126", "v127")
+#define SWCONV_EXIT_IF_LAST(LIMIT, LABEL) "s_cmp_lt_i32 %[steps], " #LIMIT "\ns_cbranch_scc1 " LABEL "%=\n"
+
+__device__ __forceinline__ void unit_rolling(uint32_t lane_base, const u32x2_t& b0, const u32x2_t& b1, int steps, Acc4& acc) {
+  asm volatile(
+      "s_nop 1\n"
+      SWCONV_READ("%[o0]", 0, SWCONV_X0, "v112") SWCONV_READ("%[o0]", 1, SWCONV_X1, "v116")
+      SWCONV_READ("%[o0]", 2, SWCONV_X2, "v120") SWCONV_READ("%[o0]", 3, SWCONV_X3, "v124")
+      SWCONV_EXIT_IF_LAST(5, "Lg0_")
+      SWCONV_GROUP_ROLL("%[w0]", "%[o0]", 0, 1, 2, 3, 4, 5, 6, 7)
+      SWCONV_EXIT_IF_LAST(9, "Lg1_")
+      SWCONV_GROUP_ROLL("%[w0]", "%[o0]", 4, 5, 6, 7, 8, 9, 10, 11)
+      SWCONV_EXIT_IF_LAST(13, "Lg2_")
+      SWCONV_GROUP_ROLL("%[w0]", "%[o0]", 8, 9, 10, 11, 12, 13, 14, 15)
+      SWCONV_EXIT_IF_LAST(17, "Lg3_")
+      SWCONV_GROUP_ROLL("%[w0]", "%[o1]", 12, 13, 14, 15, 0, 1, 2, 3)
+      SWCONV_EXIT_IF_LAST(21, "Lg4_")
+      SWCONV_GROUP_ROLL("%[w1]", "%[o1]", 0, 1, 2, 3, 4, 5, 6, 7)
+      SWCONV_EXIT_IF_LAST(25, "Lg5_")
+      SWCONV_GROUP_ROLL("%[w1]", "%[o1]", 4, 5, 6, 7, 8, 9, 10, 11)
+      SWCONV_EXIT_IF_LAST(29, "Lg6_")
+      SWCONV_GROUP_ROLL("%[w1]", "%[o1]", 8, 9, 10, 11, 12, 13, 14, 15)
+      SWCONV_GROUP_LAST("%[w1]", 12, 13, 14, 15)
+      "s_branch Lend_%=\n"
+      "Lg6_%=:\n" SWCONV_GROUP_LAST("%[w1]", 8, 9, 10, 11) "s_branch Lend_%=\n"
+      "Lg5_%=:\n" SWCONV_GROUP_LAST("%[w1]", 4, 5, 6, 7) "s_branch Lend_%=\n"
+      "Lg4_%=:\n" SWCONV_GROUP_LAST("%[w1]", 0, 1, 2, 3) "s_branch Lend_%=\n"
+      "Lg3_%=:\n" SWCONV_GROUP_LAST("%[w0]", 12, 13, 14, 15) "s_branch Lend_%=\n"
+      "Lg2_%=:\n" SWCONV_GROUP_LAST("%[w0]", 8, 9, 10, 11) "s_branch Lend_%=\n"
+      "Lg1_%=:\n" SWCONV_GROUP_LAST("%[w0]", 4, 5, 6, 7) "s_branch Lend_%=\n"
+      "Lg0_%=:\n" SWCONV_GROUP_LAST("%[w0]", 0, 1, 2, 3)
+      "Lend_%=:\n"
+      : [a0] "+v"(acc.a0), [a1] "+v"(acc.a1), [a2] "+v"(acc.a2), [a3] "+v"(acc.a3)
+      : [o0] "v"(b0.x), [w0] "v"(b0.y), [o1] "v"(b1.x), [w1] "v"(b1.y), [lb] "v"(lane_base), [steps] "s"(steps)
+      : "memory", "scc", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123",
+        "v124", "v125", "v126", "v127");
+}
+#undef SWCONV_EXIT_IF_LAST
+#undef SWCONV_GROUP_LAST
+#undef SWCONV_GROUP_ROLL
+#undef SWCONV_READ
+#undef SWCONV_FMA4
+#undef SWCONV_DPP
+#undef SWCONV_X0
+#undef SWCONV_X1
+#undef SWCONV_X2
+#undef SWCONV_X3
+
+// Row a of A^T of F(4,3) at column i: (1, p, p^2, p^3) for the points p = 0, 1, -1, 2, -2 and
+// (0, 0, 0, 1) for the point at infinity (i = 5).
+__device__ __forceinline__ void at_column(int i, float (&c)[4]) {
+  const float pt = i == 1 ? 1.0f : i == 2 ? -1.0f : i == 3 ? 2.0f : i == 4 ? -2.0f : 0.0f;
+  c[0] = i < 5 ? 1.0f : 0.0f;
+  c[1] = pt;
+  c[2] = pt * pt;
+  c[3] = pt * pt * pt + (i == 5 ? 1.0f : 0.0f);
+}
+
+template <int R, int G>
+__global__ __launch_bounds__(kFusedWaves * 64) void product_output4_kernel(
+    const float* __restrict__ V, float* __restrict__ out, const uint32_t* __restrict__ wpk, uint32_t wpk_bytes,
+    const uint8_t* __restrict__ lens, const TileInfo* __restrict__ tiles, const BlockImage* __restrict__ blocks,
+    int KC, int B, int n_wgs, const Geometry g) {
+  static_assert(R == 3, "F(4x4,3x3)");
+  constexpr int t = R + 3, P = t * t, NW = kFusedWaves, TB = kTileBlock;
+  static_assert(P <= 64 && P % 2 == 0, "one lane per position holds the slice length; positions run in pairs");
+  static_assert(G >= 1 && (G - 1) * NW * 4 < kFused4MaxC, "G direct loads per wave cover up to 64 G rows");
+  __shared__ __attribute__((aligned(1024))) float panel_even[kFused4MaxC * TB];  // panels of the even positions
+  __shared__ __attribute__((aligned(1024))) float panel_odd[kFused4MaxC * TB];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int quarter = lane >> 4;
+  const uint32_t lane_sub = (uint32_t)(lane & 15) * 16u;
+  const int vid = xcd_contiguous_id(blockIdx.x, n_wgs);  // the KC workgroups of a tile block are neighbours on one XCD
+  const int tb = vid / KC, kc = vid - tb * KC;
+  const int C = g.C, Tp = g.Tp;
+  const __amdgpu_buffer_rsrc_t wr = make_rsrc(wpk, wpk_bytes), vr = make_rsrc(V, g.v_bytes);
+
+  // the lane's view of its wave's slice lengths: lane l holds the length at position l
+  const int spp = KC * NW;
+  const int lens_v = lane < P ? (int)lens[(size_t)lane * spp + kc * NW + wave] : 0;
+
+  // Panel loads: load u of wave w moves the row group 16 u + w (rows 4 (16 u + w) .. + 3), or group
+  // 0 again where the panel has no such group; lane l fetches piece l % 16 of row l / 16 of them.
+  const uint32_t voff = ((uint32_t)(lane >> 4) * (uint32_t)Tp) * 4u + lane_sub;
+  int group_of[G];
+#pragma unroll
+  for (int u = 0; u < G; ++u) group_of[u] = u * NW + wave < C / 4 ? u * NW + wave : 0;
+  auto fetch_panel = [&](int p, float* dst) {
+    const uint32_t soff = ((uint32_t)p * C * Tp + (uint32_t)tb * TB) * 4u;
+#pragma unroll
+    for (int u = 0; u < G; ++u)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vr, (lds_ptr_t)(dst + group_of[u] * 256), 16, (int)voff,
+                                               (int)(soff + (uint32_t)group_of[u] * (uint32_t)Tp * 16u), 0, 0);
+  };
+
+  // weight batches of this wave: position p, batch b at ((p KC + kc) B + b) * NW * 512 + wave * 512
+  const uint32_t lane8 = (uint32_t)lane * 8u;
+  const uint32_t pos_bytes = (uint32_t)KC * B * NW * 512u;
+  const uint32_t w0 = ((uint32_t)kc * B * NW + wave) * 512u;
+  constexpr uint32_t kBatchStride = NW * 512u;
+  auto load_batch = [&](uint32_t byte_off) -> u32x2_t {
+    return __builtin_amdgcn_raw_buffer_load_b64(wr, (int)lane8, (int)byte_off, 0);  // past the end: reads 0
+  };
+
+  Acc4 y[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) y[a][b] = Acc4{0.0f, 0.0f, 0.0f, 0.0f};
+  Acc4 r0 = {0.0f, 0.0f, 0.0f, 0.0f}, r1 = r0, r2 = r0, r3 = r0;  // sum_j A^T[b][j] M[(i,j)], b = 0 .. 3
+
+  // One position: its panel is in `panel`, its first two weight batches in (c0, c1); meanwhile the
+  // panel of the next position goes into `other` and its first batches into (n0, n1).
+  auto position = [&](int p, const float* panel, float* other, u32x2_t& c0, u32x2_t& c1, u32x2_t& n0, u32x2_t& n1) {
+    // every wave has finished position p - 1 (which read the array that is filled next) and has
+    // waited for its share of panel p
+    __syncthreads();
+    const uint32_t cur = (uint32_t)p * pos_bytes + w0;
+    const uint32_t nxt = p + 1 < P ? cur + pos_bytes : 0xffff0000u;  // parked past the end after the last position
+    if (p + 1 < P) fetch_panel(p + 1, other);
+    n0 = load_batch(nxt);
+    n1 = load_batch(nxt + kBatchStride);
+    // an empty slice runs one group of steps on all-zero pairs: no branch around the pipeline
+    const int len = max(__builtin_amdgcn_readlane(lens_v, p), kStepGroup);
+    const int units = (len + kUnitSteps - 1) / kUnitSteps;
+    const uint32_t lane_base = (uint32_t)(uintptr_t)(lds_ptr_t)panel + lane_sub;
+    Acc4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    unit_rolling(lane_base, c0, c1, min(len, kUnitSteps), acc);
+    for (int u = 1; u < units; ++u) {  // a slice of more than 32 steps: further batches, fetched as they are needed
+      const u32x2_t e0 = load_batch(cur + (uint32_t)(2 * u) * kBatchStride);
+      const u32x2_t e1 = load_batch(cur + (uint32_t)(2 * u + 1) * kBatchStride);
+      unit_rolling(lane_base, e0, e1, min(len - u * kUnitSteps, kUnitSteps), acc);
+    }
+    // column j of A^T
+    const int j = p % t;
+    float cc[4];
+    at_column(j, cc);
+    acc_fma(r0, cc[0], acc);
+    acc_fma(r1, cc[1], acc);
+    acc_fma(r2, cc[2], acc);
+    acc_fma(r3, cc[3], acc);
+    if (j == t - 1) {  // row i of positions is complete: Y[a][b] += A^T[a][i] * r_b
+      float rc[4];
+      at_column(p / t, rc);
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        acc_fma(y[a][0], rc[a], r0);
+        acc_fma(y[a][1], rc[a], r1);
+        acc_fma(y[a][2], rc[a], r2);
+        acc_fma(y[a][3], rc[a], r3);
+      }
+      r0 = r1 = r2 = r3 = Acc4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+    // this wave's share of panel p + 1 is in LDS and the next batches are in their registers (both
+    // were asked for a whole position ago)
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+  };
+
+  fetch_panel(0, panel_even);
+  u32x2_t ca0 = load_batch(w0), ca1 = load_batch(w0 + kBatchStride), cb0 = {0u, 0u}, cb1 = {0u, 0u};
+  __builtin_amdgcn_s_waitcnt(0x0f70);
+  for (int p = 0; p < P; p += 2) {
+    position(p, panel_even, panel_odd, ca0, ca1, cb0, cb1);
+    position(p + 1, panel_odd, panel_even, cb0, cb1, ca0, ca1);
+  }
+
+  // Epilogue.  Every wave has an LDS area laid out like the output rows its tile block covers (the
+  // tables of the stand-alone output transform say where a tile's pixels go and which runs of whole
+  // rows the block has in each image), eight waves per panel array.  Row by row of W_F: the 16
+  // lanes of the row's quarter drop their 4 x 4 outputs there, then all 64 lanes write the runs out
+  // with lane-contiguous stores.  LDS executes a wave's operations in order, so inside a wave no
+  // barrier is needed.
+  __syncthreads();  // every wave is done with the panels
+  float* my = (wave < NW / 2 ? panel_even : panel_odd) + (size_t)(wave % (NW / 2)) * g.out_area;
+  const TileInfo* ti = tiles + (size_t)tb * TB + (lane & 15) * 4;
+  const TileInfo ti0 = ti[0], ti1 = ti[1], ti2 = ti[2], ti3 = ti[3];
+  const BlockImage* bi = blocks + (size_t)tb * g.slots;
+  const size_t plane = (size_t)g.Ho * g.Wo;
+  for (int q = 0; q < kSliceRows; ++q) {
+    const int k = kc * kFusedRows + wave * kSliceRows + q;  // wave-uniform
+    if (k >= g.K) break;
+    if (quarter == q) {
+      auto drop = [&](const TileInfo& tile, auto pick) {
+        const int y0 = (int16_t)(tile.yx0 & 0xffff), x0 = tile.yx0 >> 16;
+        // rows / columns of the tile inside the output (<= 0 for a padding tile, whose y0 is -32768)
+        const int rows = y0 == -32768 ? 0 : g.Ho - (y0 + g.pad), cols = g.Wo - (x0 + g.pad);
+        float* px = my + tile.out_org;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            if (a < rows && b < cols) px[a * g.Wo + b] = pick(y[a][b]);
+      };
+      drop(ti0, [](const Acc4& v) { return v.a0; });
+      drop(ti1, [](const Acc4& v) { return v.a1; });
+      drop(ti2, [](const Acc4& v) { return v.a2; });
+      drop(ti3, [](const Acc4& v) { return v.a3; });
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the drops are in LDS before any lane reads them
+    for (int sidx = 0; sidx < g.slots; ++sidx) {
+      const BlockImage b = bi[sidx];
+      if (b.n < 0) continue;
+      const float* src = my + b.out_off;
+      float* dst = out + (size_t)b.n * g.out_image_stride + k * plane + b.out_elem0;
+      // stores past the part's end are dropped by the descriptor: no lane predicate
+      const __amdgpu_buffer_rsrc_t orr = make_rsrc(dst, (uint32_t)b.out_span * 4u);
+      if (b.whole) {
+        for (int e0 = 0; e0 < b.out_span; e0 += 64)
+          buffer_store_f32<SWCONV_AUX_OUT>(orr, lane * 4u, e0 * 4u, src[e0 + lane]);
+      } else {
+        const int row_first = b.out_elem0 / g.Wo;  // wave-uniform
+        for (int e0 = 0; e0 < b.out_span; e0 += 64) {
+          const int e = e0 + lane;
+          const int ry = (int)__umulhi((uint32_t)e, g.wo_magic), x = e - ry * g.Wo;
+          const int tl = ((row_first + ry) >> g.m_shift) * g.tw + (x >> g.m_shift);
+          const bool mine = tl >= b.t_lo && tl <= b.t_hi;  // a pixel of a tile of this block
+          buffer_store_f32<SWCONV_AUX_OUT>(orr, mine ? lane * 4u : 0xfffffff0u, e0 * 4u, src[e]);
+        }
+      }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the reads are done before the next row's drops
+  }
+}
+
 }  // namespace swconv

@@ -200,6 +200,66 @@ def test_density_sweep(name, density):
                          stages=False)
 
 
+FUSED4 = [
+    # N, C, H, W, K, pad, density: F(4x4,3x3) with steps 2 and 3 in one kernel (C a multiple of 4, at most 256)
+    (5, 8, 13, 13, 10, 1, 0.3),       # ragged 13 x 13 tiles, one row chunk, K below a slice multiple
+    (3, 64, 16, 16, 70, 1, 0.1),      # whole tiles (Wo = 16), two row chunks, the second mostly padding rows
+    (2, 256, 9, 12, 130, 1, 0.3),     # rows longer than two batches (mean 77 entries), three row chunks
+    (9, 4, 8, 8, 64, 0, 1.0),         # one direct load per panel, full rows, no padding: Ho = Wo = 6
+    (1, 256, 5, 7, 5, 1, 0.05),       # the largest C the two panel arrays hold; many empty rows
+    (2, 200, 6, 6, 9, 1, 0.2),        # C not a multiple of 64: waves without a row group in the last direct load
+    (30, 12, 4, 4, 4, 1, 0.5),        # one tile per image: 30 image parts in the staging area of a wave
+]
+
+
+@pytest.mark.parametrize("N,C,H,W,K,pad,density", FUSED4)
+def test_f4x4_product_and_output_transform_in_one_kernel(N, C, H, W, K, pad, density, monkeypatch):
+    m = 4
+    x = synth.activations(N, C, H, W, 8100 + C)
+    rp, ci, va = synth.bernoulli_weights(36, K, C, density, 8200 + K)
+    outs = {}
+    for mode in ("2", "0"):
+        with monkeypatch.context() as mp:
+            mp.setenv("SWCONV_FUSE_OUTPUT", mode)
+            L = GpuLayer(N, C, H, W, K, m, 3, pad)
+            try:
+                L.set_weights(rp, ci, va)
+                outs[mode] = L.forward(x).copy()
+                ms = sw.swconv_profile_forward(L.plan, torch.cuda.current_stream().cuda_stream, L.x.data_ptr(),
+                                               L.out.data_ptr(), 2)
+                assert (ms[2] == 0) == (mode == "2"), "the fused kernel must run exactly when asked for"
+                if mode == "2":
+                    np.testing.assert_array_equal(L.out.cpu().numpy(), outs[mode])   # deterministic
+            finally:
+                L.close()
+    with monkeypatch.context() as mp:
+        mp.setenv("SWCONV_FUSE_OUTPUT", "2")
+        got = check_against_oracle(N, C, H, W, K, m, pad, x, rp, ci, va)            # V, M (step 2 run alone) and output
+    np.testing.assert_array_equal(got, outs["2"])
+    scale = np.abs(outs["0"]).max()
+    assert np.abs(outs["2"] - outs["0"]).max() <= 2 * RTOL[m] * scale
+
+
+def test_f4x4_fused_kernel_integer_data_bit_exact_and_skewed_rows(monkeypatch):
+    monkeypatch.setenv("SWCONV_FUSE_OUTPUT", "2")
+    N, C, H, W, K, m = 6, 24, 13, 13, 150, 4
+    x, rp, ci, va = synth.integer_case(N, C, H, W, K, m, 3, 0.4, 8301)
+    o64, _, _ = oracle.forward_f64(x, rp, ci, va, K, m, want_VM=False)
+    L = GpuLayer(N, C, H, W, K, m)
+    try:
+        L.set_weights(rp, ci, va)
+        np.testing.assert_array_equal(L.forward(x).astype(np.float64), o64)
+        ms = sw.swconv_profile_forward(L.plan, 0, L.x.data_ptr(), L.out.data_ptr(), 1)
+        assert ms[2] == 0
+    finally:
+        L.close()
+    # rows from empty to full inside one position (slices whose rows differ widely in length)
+    N, C, K = 4, 128, 96
+    x = synth.activations(N, C, H, W, 8302)
+    rp, ci, va = synth.skewed_weights(36, K, C, 8303)
+    check_against_oracle(N, C, H, W, K, m, 1, x, rp, ci, va)
+
+
 def test_vgg_shaped_layer_full_size():
     cfg, x, rp, ci, va = synth.make_layer("vgg_56_n32_f4")
     check_against_oracle(cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"], cfg["m"], cfg["pad"], x, rp, ci, va,
