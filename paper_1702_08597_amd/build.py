@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswconv.so")
 SOURCES = [os.path.join(CSRC, "swconv.hip")]
-HEADERS = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".hpp")]
+HEADERS = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hpp", ".inc"))]
 HEADERS.append(os.path.join(os.path.dirname(HERE), "include", "swconv.h"))
 
 # -packed-fp32-ops: keep hipcc from forming packed fp32 VALU instructions (the host pass prints a

@@ -219,89 +219,11 @@ __global__ __launch_bounds__(kFusedWaves * 64) void product_output_kernel(
 constexpr int kFused4MaxBatches = 14;  // steps of a slice must fit the 8-bit length table
 constexpr int kFused4MaxC = 256;       // rows of a panel array
 constexpr int kFused4MaxOutArea = kFused4MaxC * kTileBlock / (kFusedWaves / 2);  // floats per wave: eight waves per array
-constexpr int kUnitSteps = 2 * kBatchSteps;
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-// The first `steps` (a multiple of four, 4 .. 32, wave-uniform) step slots of one unit: slot s takes
-// its (row offset, weight) pair from lane s % 16 of the lane's quarter, in (o0, w0) for s < 16 and
-// (o1, w1) above, reads the 16 bytes at LDS address `lane_base` + row offset and adds weight times
-// those four values to acc.  Rolling pipeline: the reads of slots 0 .. 3 go out first; after the
-// multiply-adds of slot s the read of slot s + 4 is issued into the registers slot s has just
-// released (v[112:127], four registers per read in flight); the last group only multiplies.
-// LDS returns a wave's reads in order, so "all but the three youngest" is the wait for the oldest.
-// A row broadcast operand (DPP) must not follow a vector-ALU write of the same register within two
-// wait states: the pairs are only ever written by memory loads, and the block starts with two.
-#define SWCONV_X0 "v[112:115]"
-#define SWCONV_X1 "v[116:119]"
-#define SWCONV_X2 "v[120:123]"
-#define SWCONV_X3 "v[124:127]"
-#define SWCONV_DPP(N) " row_newbcast:" #N " row_mask:0xf bank_mask:0xf\n"
-#define SWCONV_FMA4(W, N, A, B, C, D)                          \
-  "v_fmac_f32_dpp %[a0], " W ", " A SWCONV_DPP(N)              \
-  "v_fmac_f32_dpp %[a1], " W ", " B SWCONV_DPP(N)              \
-  "v_fmac_f32_dpp %[a2], " W ", " C SWCONV_DPP(N)              \
-  "v_fmac_f32_dpp %[a3], " W ", " D SWCONV_DPP(N)
-#define SWCONV_READ(O, N, XT, XA) "v_add_u32_dpp " XA ", " O ", %[lb]" SWCONV_DPP(N) "ds_read_b128 " XT ", " XA "\n"
-// one group of four slots that is not the slice's last: multiply-adds of lanes N0 .. N3 (weights in W),
-// then the reads of lanes M0 .. M3 (offsets in O)
-#define SWCONV_GROUP_ROLL(W, O, N0, N1, N2, N3, M0, M1, M2, M3)                                            \
-  "s_waitcnt lgkmcnt(3)\n" SWCONV_FMA4(W, N0, "v112", "v113", "v114", "v115") SWCONV_READ(O, M0, SWCONV_X0, "v112") \
-  "s_waitcnt lgkmcnt(3)\n" SWCONV_FMA4(W, N1, "v116", "v117", "v118", "v119") SWCONV_READ(O, M1, SWCONV_X1, "v116") \
-  "s_waitcnt lgkmcnt(3)\n" SWCONV_FMA4(W, N2, "v120", "v121", "v122", "v123") SWCONV_READ(O, M2, SWCONV_X2, "v120") \
-  "s_waitcnt lgkmcnt(3)\n" SWCONV_FMA4(W, N3, "v124", "v125", "v126", "v127") SWCONV_READ(O, M3, SWCONV_X3, "v124")
-// the slice's last group: the pipeline drains
-#define SWCONV_GROUP_LAST(W, N0, N1, N2, N3)                                       \
-  "s_waitcnt lgkmcnt(3)\n" SWCONV_FMA4(W, N0, "v112", "v113", "v114", "v115")      \
-  "s_waitcnt lgkmcnt(2)\n" SWCONV_FMA4(W, N1, "v116", "v117", "v118", "v119")      \
-  "s_waitcnt lgkmcnt(1)\n" SWCONV_FMA4(W, N2, "v120", "v121", "v122", "v123")      \
-  "s_waitcnt lgkmcnt(0)\n" SWCONV_FMA4(W, N3, "v124", "v125", "v126", "v127")
-#define SWCONV_EXIT_IF_LAST(LIMIT, LABEL) "s_cmp_lt_i32 %[steps], " #LIMIT "\ns_cbranch_scc1 " LABEL "%=\n"
-
-__device__ __forceinline__ void unit_rolling(uint32_t lane_base, const u32x2_t& b0, const u32x2_t& b1, int steps, Acc4& acc) {
-  asm volatile(
-      "s_nop 1\n"
-      SWCONV_READ("%[o0]", 0, SWCONV_X0, "v112") SWCONV_READ("%[o0]", 1, SWCONV_X1, "v116")
-      SWCONV_READ("%[o0]", 2, SWCONV_X2, "v120") SWCONV_READ("%[o0]", 3, SWCONV_X3, "v124")
-      SWCONV_EXIT_IF_LAST(5, "Lg0_")
-      SWCONV_GROUP_ROLL("%[w0]", "%[o0]", 0, 1, 2, 3, 4, 5, 6, 7)
-      SWCONV_EXIT_IF_LAST(9, "Lg1_")
-      SWCONV_GROUP_ROLL("%[w0]", "%[o0]", 4, 5, 6, 7, 8, 9, 10, 11)
-      SWCONV_EXIT_IF_LAST(13, "Lg2_")
-      SWCONV_GROUP_ROLL("%[w0]", "%[o0]", 8, 9, 10, 11, 12, 13, 14, 15)
-      SWCONV_EXIT_IF_LAST(17, "Lg3_")
-      SWCONV_GROUP_ROLL("%[w0]", "%[o1]", 12, 13, 14, 15, 0, 1, 2, 3)
-      SWCONV_EXIT_IF_LAST(21, "Lg4_")
-      SWCONV_GROUP_ROLL("%[w1]", "%[o1]", 0, 1, 2, 3, 4, 5, 6, 7)
-      SWCONV_EXIT_IF_LAST(25, "Lg5_")
-      SWCONV_GROUP_ROLL("%[w1]", "%[o1]", 4, 5, 6, 7, 8, 9, 10, 11)
-      SWCONV_EXIT_IF_LAST(29, "Lg6_")
-      SWCONV_GROUP_ROLL("%[w1]", "%[o1]", 8, 9, 10, 11, 12, 13, 14, 15)
-      SWCONV_GROUP_LAST("%[w1]", 12, 13, 14, 15)
-      "s_branch Lend_%=\n"
-      "Lg6_%=:\n" SWCONV_GROUP_LAST("%[w1]", 8, 9, 10, 11) "s_branch Lend_%=\n"
-      "Lg5_%=:\n" SWCONV_GROUP_LAST("%[w1]", 4, 5, 6, 7) "s_branch Lend_%=\n"
-      "Lg4_%=:\n" SWCONV_GROUP_LAST("%[w1]", 0, 1, 2, 3) "s_branch Lend_%=\n"
-      "Lg3_%=:\n" SWCONV_GROUP_LAST("%[w0]", 12, 13, 14, 15) "s_branch Lend_%=\n"
-      "Lg2_%=:\n" SWCONV_GROUP_LAST("%[w0]", 8, 9, 10, 11) "s_branch Lend_%=\n"
-      "Lg1_%=:\n" SWCONV_GROUP_LAST("%[w0]", 4, 5, 6, 7) "s_branch Lend_%=\n"
-      "Lg0_%=:\n" SWCONV_GROUP_LAST("%[w0]", 0, 1, 2, 3)
-      "Lend_%=:\n"
-      : [a0] "+v"(acc.a0), [a1] "+v"(acc.a1), [a2] "+v"(acc.a2), [a3] "+v"(acc.a3)
-      : [o0] "v"(b0.x), [w0] "v"(b0.y), [o1] "v"(b1.x), [w1] "v"(b1.y), [lb] "v"(lane_base), [steps] "s"(steps)
-      : "memory", "scc", "v112", "v113", "v114", "v115", "v116", "v117", "v118", "v119", "v120", "v121", "v122", "v123",
-        "v124", "v125", "v126", "v127");
-}
-#undef SWCONV_EXIT_IF_LAST
-#undef SWCONV_GROUP_LAST
-#undef SWCONV_GROUP_ROLL
-#undef SWCONV_READ
-#undef SWCONV_FMA4
-#undef SWCONV_DPP
-#undef SWCONV_X0
-#undef SWCONV_X1
-#undef SWCONV_X2
-#undef SWCONV_X3
+// The rolling unit of the inner loop (unit_rolling_hi: its reads in flight live in v[112:127]) is
+// defined in swconv_kernels.hpp.
 
 // Row a of A^T of F(4,3) at column i: (1, p, p^2, p^3) for the points p = 0, 1, -1, 2, -2 and
 // (0, 0, 0, 1) for the point at infinity (i = 5).
@@ -383,11 +305,11 @@ __global__ __launch_bounds__(kFusedWaves * 64) void product_output4_kernel(
     const int units = (len + kUnitSteps - 1) / kUnitSteps;
     const uint32_t lane_base = (uint32_t)(uintptr_t)(lds_ptr_t)panel + lane_sub;
     Acc4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-    unit_rolling(lane_base, c0, c1, min(len, kUnitSteps), acc);
+    unit_rolling_hi(lane_base, c0, c1, min(len, kUnitSteps), acc);
     for (int u = 1; u < units; ++u) {  // a slice of more than 32 steps: further batches, fetched as they are needed
       const u32x2_t e0 = load_batch(cur + (uint32_t)(2 * u) * kBatchStride);
       const u32x2_t e1 = load_batch(cur + (uint32_t)(2 * u + 1) * kBatchStride);
-      unit_rolling(lane_base, e0, e1, min(len - u * kUnitSteps, kUnitSteps), acc);
+      unit_rolling_hi(lane_base, e0, e1, min(len - u * kUnitSteps, kUnitSteps), acc);
     }
     // column j of A^T
     const int j = p % t;

@@ -362,6 +362,48 @@ __device__ __forceinline__ void quarter_batch(const float* panel, uint32_t lane_
   if (steps > 3 * kStepGroup) quarter_group<3>(panel, lane_sub, b.x, b.y, acc);
 }
 
+// The rolling unit of the inner loop (see swconv_rolling_unit.inc): the same steps as quarter_batch over
+// two batches, as one pipeline with four reads always in flight, in assembly with the sixteen registers
+// of those reads fixed: v[112:127], the top of the 128 registers of the fused F(4x4,3x3) kernel, whose
+// other registers are full of accumulators.  (In the stand-alone product kernel below the compiler's
+// group-by-group code is as fast: there memory, not the inner loop, sets the pace.)
+constexpr int kUnitSteps = 2 * kBatchSteps;
+#define SWCONV_UNIT_NAME unit_rolling_hi
+#define SWCONV_XR0 112
+#define SWCONV_XR1 113
+#define SWCONV_XR2 114
+#define SWCONV_XR3 115
+#define SWCONV_XR4 116
+#define SWCONV_XR5 117
+#define SWCONV_XR6 118
+#define SWCONV_XR7 119
+#define SWCONV_XR8 120
+#define SWCONV_XR9 121
+#define SWCONV_XR10 122
+#define SWCONV_XR11 123
+#define SWCONV_XR12 124
+#define SWCONV_XR13 125
+#define SWCONV_XR14 126
+#define SWCONV_XR15 127
+#include "swconv_rolling_unit.inc"
+#undef SWCONV_UNIT_NAME
+#undef SWCONV_XR0
+#undef SWCONV_XR1
+#undef SWCONV_XR2
+#undef SWCONV_XR3
+#undef SWCONV_XR4
+#undef SWCONV_XR5
+#undef SWCONV_XR6
+#undef SWCONV_XR7
+#undef SWCONV_XR8
+#undef SWCONV_XR9
+#undef SWCONV_XR10
+#undef SWCONV_XR11
+#undef SWCONV_XR12
+#undef SWCONV_XR13
+#undef SWCONV_XR14
+#undef SWCONV_XR15
+
 // ---- sampled mode (backward pass, Eq. 5 second line): dL/dW_F at the stored entries ----
 // The same walk over the packed W_F, but instead of accumulating w * x into the row, every stored
 // entry (k, c) gets the dot product of dL/dZ[p][k][.] with the panel row of c over the 64 tiles of
