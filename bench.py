@@ -381,6 +381,25 @@ def main():
                 sw.swconv_plan_destroy(p2)
             del keep
 
+    if not args.dense:
+        # What this machine's memory system gives a plain device-to-device copy of 1 GiB (read + written bytes per
+        # second): the practical ceiling next to the published 8 TB/s that the fractions above are taken against.
+        n = (1 << 30) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record(stream)
+        e1.synchronize()
+        copy_gbs = 2 * n * 4 * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        result["device_copy"] = {"GBps": round(copy_gbs, 1), "frac_of_peak": round(copy_gbs / HBM_PEAK_GBS, 4),
+                                 "what": "torch copy_ of 1 GiB, bytes read + written"}
+        del src, dst
+
     if not args.no_cpu_baseline:
         import oracle
 
