@@ -37,11 +37,25 @@ def test_status_strings():
     ((1, 4, 8, 8, 4, 3, 3, 1), sw.SWCONV_EUNSUPPORTED),  # F(3,3)
     ((1, 4, 8, 8, 4, 6, 5, 1), sw.SWCONV_EUNSUPPORTED),  # F(6,5): m = 2 and 4 are built for r = 5
     ((1, 4096, 8, 8, 4, 4, 3, 1), sw.SWCONV_EUNSUPPORTED),  # panel beyond LDS
+    ((1, 639, 8, 8, 4, 4, 3, 1), sw.SWCONV_EUNSUPPORTED),   # the first channel count whose panel does not fit
 ])
 def test_plan_create_rejects(args, status):
     with pytest.raises(sw.SwconvError) as e:
         sw.swconv_plan_create(*args)
     assert e.value.status == status
+
+
+def test_largest_panel_is_accepted_and_packs():
+    # C = 638: the 64-tile panel, the slice counter and the fewest slice descriptors just fit LDS
+    pl = sw.swconv_plan_create(1, 638, 6, 6, 9, 4, 3, 1)
+    try:
+        rp, ci, va = synth.bernoulli_weights(36, 9, 638, 0.2, 12)
+        assert sw.swconv_set_weights_status(pl, rp, ci, va) in (sw.SWCONV_OK, sw.SWCONV_EHIP)   # EHIP: no device here
+        rp2, ci2, va2 = sw.swconv_debug_export_weights(pl, 9, int(rp[-1]))
+        np.testing.assert_array_equal(ci2, ci)
+        sw.swconv_debug_check_schedule(pl)
+    finally:
+        sw.swconv_plan_destroy(pl)
 
 
 def test_plan_sizes():
