@@ -260,6 +260,24 @@ def test_f4x4_fused_kernel_integer_data_bit_exact_and_skewed_rows(monkeypatch):
     check_against_oracle(N, C, H, W, K, m, 1, x, rp, ci, va)
 
 
+def test_vgg_shaped_layer_full_size_through_the_fused_f4x4_kernel(monkeypatch):
+    # the launch configuration the profiles of the fused kernel were taken in: 98 tile blocks x 4 row chunks
+    monkeypatch.setenv("SWCONV_FUSE_OUTPUT", "2")
+    cfg, x, rp, ci, va = synth.make_layer("vgg_56_n32_f4")
+    out = check_against_oracle(cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"], cfg["m"], cfg["pad"], x, rp, ci, va,
+                               stages=False)
+    plan = sw.swconv_plan_create(cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"], cfg["m"], 3, cfg["pad"])
+    try:
+        sw.swconv_set_weights(plan, rp, ci, va)
+        xd = torch.from_numpy(x).cuda()
+        od = torch.empty(out.shape, device="cuda")
+        ms = sw.swconv_profile_forward(plan, 0, xd.data_ptr(), od.data_ptr(), 1)
+        assert ms[2] == 0, "the fused kernel did not run"
+        np.testing.assert_array_equal(od.cpu().numpy(), out)
+    finally:
+        sw.swconv_plan_destroy(plan)
+
+
 def test_vgg_shaped_layer_full_size():
     cfg, x, rp, ci, va = synth.make_layer("vgg_56_n32_f4")
     check_against_oracle(cfg["N"], cfg["C"], cfg["H"], cfg["W"], cfg["K"], cfg["m"], cfg["pad"], x, rp, ci, va,

@@ -207,3 +207,17 @@ def test_schedule_is_a_partition_for_random_shapes_and_cost_settings(seed, env, 
         np.testing.assert_array_equal(ci2, ci)
         np.testing.assert_array_equal(va2.view(np.uint32), va.view(np.uint32))
         sw.swconv_plan_destroy(pl)
+
+
+def test_product_path_never_touches_the_oracle():
+    """The package (binding, build script, input generators, kernels) must not import, include, load or run
+    anything under oracle/: the oracle is the checker, and a product path through it would void every parity test."""
+    pkg = os.path.join(ROOT, "paper_1702_08597_amd")
+    for folder, _, files in os.walk(pkg):
+        for name in files:
+            if not name.endswith((".py", ".hip", ".hpp", ".inc", ".h")):
+                continue
+            text = open(os.path.join(folder, name), encoding="utf-8", errors="replace").read()
+            assert not re.search(r"\boracle\b(?!s)", text.replace("the CPU oracle", "")), "%s names the oracle" % name
+    header = open(os.path.join(ROOT, "include", "swconv.h")).read()
+    assert "oracle" not in header
